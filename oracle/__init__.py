@@ -1,0 +1,212 @@
+"""ctypes binding of the fp64 CPU oracle (oracle/nosa_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by ``__graft_entry__.smoke()`` and by the
+``cpu_baseline`` leg of ``bench.py``.  The product package never imports this module, and
+this module never imports the product package.
+
+All arrays are numpy, C-contiguous, host memory.  bf16 tensors travel as ``uint16``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "nosa_oracle.c")
+_LIB = os.path.join(_HERE, "libnosa_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (OpenMP over units) into oracle/libnosa_oracle.so."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "batch", "n_q_heads", "n_kv_heads", "head_dim", "block_size", "pool_kernel", "pool_stride",
+        "k_blocks", "kq_blocks", "sink_blocks", "window_blocks", "gpu_slots", "max_blocks",
+        "n_sub_max", "dtype")] + [("softmax_scale", ctypes.c_double)]
+
+
+@dataclass
+class Params:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    k_blocks: int
+    kq_blocks: int
+    sink_blocks: int
+    window_blocks: int
+    gpu_slots: int
+    max_blocks: int
+    n_sub_max: int
+    dtype: int                      # 0 fp32, 1 bf16
+    softmax_scale: float
+    block_size: int = 64
+    pool_kernel: int = 64
+    pool_stride: int = 64
+
+    def c(self) -> _Params:
+        return _Params(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.block_size,
+                       self.pool_kernel, self.pool_stride, self.k_blocks, self.kq_blocks,
+                       self.sink_blocks, self.window_blocks, self.gpu_slots, self.max_blocks,
+                       self.n_sub_max, self.dtype, float(self.softmax_scale))
+
+    @property
+    def units(self) -> int:
+        return self.batch * self.n_kv_heads
+
+    @property
+    def np_dtype(self):
+        return np.float32 if self.dtype == 0 else np.uint16
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_num_threads.restype = ctypes.c_int
+        _lib.oracle_attention.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def set_threads(n: int) -> None:
+    lib().oracle_set_threads(ctypes.c_int(n))
+
+
+def _ptr(a: Optional[np.ndarray], dtype=None):
+    if a is None:
+        return ctypes.c_void_p(0)
+    assert isinstance(a, np.ndarray) and a.flags["C_CONTIGUOUS"], "oracle needs C-contiguous numpy arrays"
+    if dtype is not None:
+        assert a.dtype == dtype, (a.dtype, dtype)
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _check(a: np.ndarray, shape, dtype, name: str):
+    assert a.shape == tuple(shape), f"{name}: shape {a.shape} != {tuple(shape)}"
+    assert a.dtype == dtype, f"{name}: dtype {a.dtype} != {dtype}"
+
+
+def pool(p: Params, keys: np.ndarray, bias: np.ndarray, n_tokens: np.ndarray):
+    """Mean pooling of keys and of the importance score over sub-blocks (Sec. 3.1, mean-pooling Eq.)."""
+    B, H, d, nb = p.batch, p.n_kv_heads, p.head_dim, p.block_size
+    _check(keys, (B, H, p.max_blocks, nb, d), p.np_dtype, "keys")
+    _check(bias, (B, H, p.max_blocks, nb), np.float32, "bias")
+    _check(n_tokens, (B,), np.int32, "n_tokens")
+    k_pooled = np.zeros((B, H, p.n_sub_max, d), dtype=p.np_dtype)
+    se_pooled = np.zeros((B, H, p.n_sub_max), dtype=np.float32)
+    pc = p.c()
+    lib().oracle_pool(ctypes.byref(pc), _ptr(keys), _ptr(bias), _ptr(n_tokens), _ptr(k_pooled), _ptr(se_pooled))
+    return k_pooled, se_pooled
+
+
+def block_score(p: Params, q: np.ndarray, k_pooled: np.ndarray, se_pooled: np.ndarray, n_tokens: np.ndarray,
+                per_head: bool = False):
+    """Block-level query-aware and query-agnostic scores (Alg. 1, Stage 1 up to fused pooling)."""
+    B, H = p.batch, p.n_kv_heads
+    _check(q, (B, p.n_q_heads, p.head_dim), p.np_dtype, "q")
+    _check(k_pooled, (B, H, p.n_sub_max, p.head_dim), p.np_dtype, "k_pooled")
+    _check(se_pooled, (B, H, p.n_sub_max), np.float32, "se_pooled")
+    _check(n_tokens, (B,), np.int32, "n_tokens")
+    sq = np.empty((B, H, p.max_blocks), dtype=np.float64)
+    se = np.empty((B, H, p.max_blocks), dtype=np.float64)
+    head = np.zeros((B, p.n_q_heads, p.n_sub_max), dtype=np.float64) if per_head else None
+    pc = p.c()
+    lib().oracle_block_score(ctypes.byref(pc), _ptr(q), _ptr(k_pooled), _ptr(se_pooled), _ptr(n_tokens),
+                             _ptr(sq), _ptr(se), _ptr(head))
+    return (sq, se, head) if per_head else (sq, se)
+
+
+def select(p: Params, sq_blk: np.ndarray, se_blk: np.ndarray, n_tokens: np.ndarray, with_kind: bool = False):
+    """Constrained top-k block selection (selection Eq., Sec. 3.1)."""
+    B, H = p.batch, p.n_kv_heads
+    sq_blk = np.ascontiguousarray(sq_blk, dtype=np.float64)
+    se_blk = np.ascontiguousarray(se_blk, dtype=np.float64)
+    _check(sq_blk, (B, H, p.max_blocks), np.float64, "sq_blk")
+    _check(se_blk, (B, H, p.max_blocks), np.float64, "se_blk")
+    _check(n_tokens, (B,), np.int32, "n_tokens")
+    if p.sink_blocks + p.window_blocks + p.kq_blocks > p.k_blocks or p.window_blocks < 1:
+        raise ValueError("budget must satisfy Ns + Nw + Kq <= K and Nw >= 1")
+    sel = np.empty((B, H, p.k_blocks), dtype=np.int32)
+    n_sel = np.empty((B, H), dtype=np.int32)
+    kind = np.empty((B, H, p.k_blocks), dtype=np.int32) if with_kind else None
+    pc = p.c()
+    lib().oracle_select(ctypes.byref(pc), _ptr(sq_blk), _ptr(se_blk), _ptr(n_tokens), _ptr(sel), _ptr(n_sel),
+                        _ptr(kind))
+    return (sel, n_sel, kind) if with_kind else (sel, n_sel)
+
+
+def load(p: Params, sel_idx: np.ndarray, n_sel: np.ndarray, slot_of_block: np.ndarray, block_of_slot: np.ndarray):
+    """Set difference of the selection against the resident map; updates both maps in place."""
+    B, H = p.batch, p.n_kv_heads
+    _check(sel_idx, (B, H, p.k_blocks), np.int32, "sel_idx")
+    _check(n_sel, (B, H), np.int32, "n_sel")
+    _check(slot_of_block, (B, H, p.max_blocks), np.int32, "slot_of_block")
+    _check(block_of_slot, (B, H, p.gpu_slots), np.int32, "block_of_slot")
+    load_list = np.empty((B, H, p.k_blocks, 2), dtype=np.int32)
+    n_load = np.empty((B, H), dtype=np.int32)
+    pc = p.c()
+    lib().oracle_load(ctypes.byref(pc), _ptr(sel_idx), _ptr(n_sel), _ptr(slot_of_block), _ptr(block_of_slot),
+                      _ptr(load_list), _ptr(n_load))
+    return load_list, n_load
+
+
+def fetch(p: Params, host_k, host_v, host_bias, pool_k, pool_v, pool_bias, load_list, n_load) -> None:
+    """Copy the missed blocks from the host pool into their slots (in place on the pool arrays)."""
+    B, H, d, nb = p.batch, p.n_kv_heads, p.head_dim, p.block_size
+    _check(host_k, (B, H, p.max_blocks, nb, d), p.np_dtype, "host_k")
+    _check(host_v, (B, H, p.max_blocks, nb, d), p.np_dtype, "host_v")
+    _check(pool_k, (B, H, p.gpu_slots, nb, d), p.np_dtype, "pool_k")
+    _check(pool_v, (B, H, p.gpu_slots, nb, d), p.np_dtype, "pool_v")
+    if host_bias is not None:
+        _check(host_bias, (B, H, p.max_blocks, nb), np.float32, "host_bias")
+        _check(pool_bias, (B, H, p.gpu_slots, nb), np.float32, "pool_bias")
+    _check(load_list, (B, H, p.k_blocks, 2), np.int32, "load_list")
+    _check(n_load, (B, H), np.int32, "n_load")
+    pc = p.c()
+    lib().oracle_fetch(ctypes.byref(pc), _ptr(host_k), _ptr(host_v), _ptr(host_bias), _ptr(pool_k), _ptr(pool_v),
+                       _ptr(pool_bias), _ptr(load_list), _ptr(n_load))
+
+
+def attention(p: Params, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens,
+              with_probs: bool = False):
+    """Biased softmax attention over the tokens of the selected blocks (Sec. 3.1, output Eq.)."""
+    B, H, d, nb = p.batch, p.n_kv_heads, p.head_dim, p.block_size
+    _check(q, (B, p.n_q_heads, d), p.np_dtype, "q")
+    _check(pool_k, (B, H, p.gpu_slots, nb, d), p.np_dtype, "pool_k")
+    _check(pool_v, (B, H, p.gpu_slots, nb, d), p.np_dtype, "pool_v")
+    if pool_bias is not None:
+        _check(pool_bias, (B, H, p.gpu_slots, nb), np.float32, "pool_bias")
+    _check(sel_idx, (B, H, p.k_blocks), np.int32, "sel_idx")
+    _check(n_sel, (B, H), np.int32, "n_sel")
+    _check(slot_of_block, (B, H, p.max_blocks), np.int32, "slot_of_block")
+    _check(n_tokens, (B,), np.int32, "n_tokens")
+    out = np.zeros((B, p.n_q_heads, d), dtype=np.float64)
+    lse = np.zeros((B, p.n_q_heads), dtype=np.float64)
+    probs = np.zeros((B, p.n_q_heads, p.k_blocks * nb), dtype=np.float64) if with_probs else None
+    pc = p.c()
+    bad = lib().oracle_attention(ctypes.byref(pc), _ptr(q), _ptr(pool_k), _ptr(pool_v), _ptr(pool_bias),
+                                 _ptr(sel_idx), _ptr(n_sel), _ptr(slot_of_block), _ptr(n_tokens), _ptr(out),
+                                 _ptr(lse), _ptr(probs))
+    if bad:
+        raise RuntimeError(f"oracle_attention: {bad} selected blocks have no slot")
+    return (out, lse, probs) if with_probs else (out, lse)

@@ -1,0 +1,143 @@
+"""Pins for the oracle's residency / fetch model (Sec. 4 "Memory Layout and Block Selection").
+
+ - Theorem 1 (Sec. 3.1, proof in App. E): with the GPU holding exactly the previous selection
+   (C = K), every step after the first loads at most Kq blocks, i.e. locality >= (K - Kq) / K;
+   the paper's instance is 48 / 64 = 75 %.
+ - after a step every selected block has a slot, no slot is booked twice, the two maps are
+   inverse to each other, and each selected slot holds the host copy of its block byte for byte;
+ - the load list is exactly the set difference Gamma(t) \\ resident(t-1), computed here with
+   Python sets;
+ - whole-step check: scores -> selection -> load -> fetch -> attention through the pool equals
+   brute-force attention over the host cache restricted to Gamma.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import oracle_params, small_workload, to_np, widen
+from nosa_inputs import CONFIGS, QueryStream, make_layer, random_residency
+
+
+def _check_maps(p, sob, bos, sel, n_sel):
+    for b in range(p.batch):
+        for h in range(p.n_kv_heads):
+            used = bos[b, h][bos[b, h] >= 0]
+            assert len(set(used.tolist())) == len(used)                    # no block in two slots
+            for s, J in enumerate(bos[b, h]):
+                if J >= 0:
+                    assert sob[b, h, J] == s
+            for J in np.nonzero(sob[b, h] >= 0)[0]:
+                assert bos[b, h, sob[b, h, J]] == J
+            for J in sel[b, h, :n_sel[b, h]]:
+                assert sob[b, h, J] >= 0                                   # every selected block resident
+
+
+@pytest.mark.parametrize("K,Kq,Ns,Nw,C,N", [(64, 16, 1, 16, 64, 256), (64, 8, 1, 16, 64, 512), (8, 2, 1, 1, 8, 32),
+                                            (32, 8, 1, 8, 64, 128), (16, 0, 1, 3, 16, 40)])
+def test_theorem1_locality_bound_over_steps(K, Kq, Ns, Nw, C, N):
+    rng = np.random.default_rng(K * 1000 + Kq)
+    T = 64 * N
+    w = small_workload(batch=2, context=T, k_blocks=K, kq_blocks=Kq, sink_blocks=Ns, window_blocks=Nw, gpu_slots=C)
+    p = oracle_params(w)
+    n_tok = np.full((w.batch,), T, np.int32)
+    se = rng.standard_normal((w.batch, w.n_kv_heads, N))
+    sob = np.full((w.batch, w.n_kv_heads, N), -1, np.int32)
+    bos = np.full((w.batch, w.n_kv_heads, C), -1, np.int32)
+    prev = None
+    for t in range(12):
+        sq = rng.standard_normal((w.batch, w.n_kv_heads, N)) * 3          # adversarial: fresh query every step
+        sel, n_sel = oracle.select(p, sq, se, n_tok)
+        resident_before = [[set(np.nonzero(sob[b, h] >= 0)[0].tolist()) for h in range(w.n_kv_heads)]
+                           for b in range(w.batch)]
+        ll, n_load = oracle.load(p, sel, n_sel, sob, bos)
+        _check_maps(p, sob, bos, sel, n_sel)
+        for b in range(w.batch):
+            for h in range(w.n_kv_heads):
+                gamma = set(sel[b, h, :n_sel[b, h]].tolist())
+                miss = sorted(gamma - resident_before[b][h])
+                assert ll[b, h, :n_load[b, h], 0].tolist() == miss         # the set difference, ascending
+                assert (ll[b, h, n_load[b, h]:] == -1).all()
+                slots = ll[b, h, :n_load[b, h], 1]
+                assert len(set(slots.tolist())) == len(slots)
+                if t == 0:
+                    assert n_load[b, h] == K                               # cold start
+                elif C == K:
+                    assert n_load[b, h] <= Kq                              # Theorem 1
+                    g_prev = set(prev[b, h].tolist())
+                    assert len(gamma & g_prev) / len(gamma) >= (K - Kq) / K
+        prev = sel.copy()
+    if (K, Kq) == (64, 16):
+        assert (K - Kq) / K == 0.75                                        # the paper's 48/64 instance
+
+
+def test_full_step_through_pool_equals_bruteforce_on_host_cache():
+    w = CONFIGS["tiny"].replace(context=64 * 24 + 30, steps=5)
+    p = oracle_params(w)
+    seed = 13
+    layer = make_layer(w, seed, 0)
+    hk, hv, hb = to_np(layer["host_k"]), to_np(layer["host_v"]), to_np(layer["host_bias"])
+    n_tok = np.full((w.batch,), w.context, np.int32)
+    kc, sec = oracle.pool(p, hk, hb, n_tok)
+    B, H, C, nb, d = w.batch, w.n_kv_heads, w.gpu_slots, w.block_size, w.head_dim
+    pk = np.full((B, H, C, nb, d), np.nan, hk.dtype)
+    pv = np.full((B, H, C, nb, d), np.nan, hv.dtype)
+    pb = np.full((B, H, C, nb), np.nan, np.float32)
+    sob = np.full((B, H, w.max_blocks), -1, np.int32)
+    bos = np.full((B, H, C), -1, np.int32)
+    qs = QueryStream(w, seed, 0)
+    Kd, Vd = widen(hk).reshape(B, H, -1, d), widen(hv).reshape(B, H, -1, d)
+    Bd = hb.astype(np.float64).reshape(B, H, -1)
+    for t in range(w.steps):
+        q = to_np(qs.next(t))
+        sq, se = oracle.block_score(p, q, kc, sec, n_tok)
+        sel, n_sel = oracle.select(p, sq, se, n_tok)
+        ll, n_load = oracle.load(p, sel, n_sel, sob, bos)
+        if t > 0:
+            assert (n_load <= w.kq_blocks).all()
+        oracle.fetch(p, hk, hv, hb, pk, pv, pb, ll, n_load)
+        for b in range(B):
+            for h in range(H):
+                for J in sel[b, h, :n_sel[b, h]]:
+                    s = sob[b, h, J]
+                    assert pk[b, h, s].tobytes() == hk[b, h, J].tobytes()
+                    assert pv[b, h, s].tobytes() == hv[b, h, J].tobytes()
+                    assert pb[b, h, s].tobytes() == hb[b, h, J].tobytes()
+        out, _ = oracle.attention(p, q, pk, pv, pb, sel, n_sel, sob, n_tok)
+        Q = widen(q)
+        for b in range(B):
+            for hq in range(w.n_q_heads):
+                h = hq // w.group
+                mask = np.full(Kd.shape[2], -np.inf)
+                for J in sel[b, h, :n_sel[b, h]]:
+                    mask[J * nb:(J + 1) * nb] = 0
+                mask[w.context:] = -np.inf
+                z = p.softmax_scale * (Kd[b, h] @ Q[b, hq]) + Bd[b, h] + mask
+                pr = np.exp(z - z.max())
+                pr /= pr.sum()
+                np.testing.assert_allclose(out[b, hq], pr @ Vd[b, h], rtol=0, atol=1e-12)
+
+
+def test_planted_blocks_are_picked_query_aware_on_tiny():
+    """The tiny workload plants 3 high-similarity blocks; with Kq = 2 the query-aware picks are
+    two of them at every step (clear margin), and the fetch budget of 2 blocks per step holds."""
+    w = CONFIGS["tiny"]
+    p = oracle_params(w)
+    layer = make_layer(w, 0, 0)
+    hk, hb = to_np(layer["host_k"]), to_np(layer["host_bias"])
+    n_tok = np.full((w.batch,), w.context, np.int32)
+    kc, sec = oracle.pool(p, hk, hb, n_tok)
+    planted = set(layer["planted"][0, 0].tolist())
+    qs = QueryStream(w, 0, 0)
+    sob, bos = random_residency(w, 0, 0, w.max_blocks)
+    sob, bos = sob.numpy(), bos.numpy()
+    for t in range(w.steps):
+        q = to_np(qs.next(t))
+        sq, se = oracle.block_score(p, q, kc, sec, n_tok)
+        sel, n_sel, kind = oracle.select(p, sq, se, n_tok, with_kind=True)
+        picks = set(sel[0, 0][kind[0, 0] == 1].tolist())
+        assert len(picks) == 2 and picks <= planted
+        order = np.sort(sq[0, 0, 1:31])[::-1]
+        assert order[1] - order[3] > 1.0                      # planted vs the rest: wide margin
+        _, n_load = oracle.load(p, sel, n_sel, sob, bos)
+        if t > 0:
+            assert n_load[0, 0] <= 2
