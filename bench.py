@@ -1,0 +1,225 @@
+#!/usr/bin/env python3
+"""Benchmark of the NOSA decode-step hot path on one MI355X.
+
+A "step" is one pass of the whole path (block score -> constrained selection + load positions ->
+fetch of missed blocks from pinned host memory -> block-sparse attention) over one batch of one
+layer of the 8B-shaped workload (batch 64, 32 query / 8 KV heads, d 128, 32768 tokens, block 64,
+K = 64 blocks, fetch budget Kq = 8, bf16).  Successive steps cycle through distinct layers, so no
+step finds its KV pool in cache.  The metric counts (batch x KV head x layer) units per second.
+
+Prints ONE JSON line; see the design doc for the meaning of every field.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--workload", default="8b", choices=["tiny", "1b", "3b", "8b"])
+    ap.add_argument("--layers", type=int, default=0, help="distinct GPU layer states to cycle (0 = workload default, max 32)")
+    ap.add_argument("--host-layers", type=int, default=2, help="distinct pinned host pools (each 8 GiB at the 8B shape)")
+    ap.add_argument("--splits", type=int, default=0, help="override the number of attention splits")
+    ap.add_argument("--no-overlap", action="store_true", help="run the fetch on the main stream")
+    ap.add_argument("--resident", action="store_true", help="kernel-only mode: same queries every step, so nothing is fetched")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=4)
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def decode_bytes_per_unit(w) -> int:
+    """Algorithmic HBM bytes one unit costs the attention kernel per step: the K and V rows and the
+    bias of the K selected blocks, q in, o out, the selection list and its slots."""
+    e = w.elem_size
+    kv = w.k_blocks * w.block_size * (2 * w.head_dim * e + 4)
+    qo = 2 * w.group * w.head_dim * e
+    idx = 2 * w.k_blocks * 4
+    return kv + qo + idx
+
+
+def step_bytes_per_unit(w) -> int:
+    """Algorithmic HBM bytes of the whole step per unit: attention + pooled keys and importance."""
+    e = w.elem_size
+    return decode_bytes_per_unit(w) + w.n_sub_max * (w.head_dim * e + 4)
+
+
+def cpu_baseline(w, seed, sample_batch, steps=2):
+    """The fp64 oracle, as it stands, timed on this machine's host cores on a slice of the same workload."""
+    import numpy as np
+    import oracle
+    from nosa_inputs import QueryStream, make_layer
+    oracle_params, to_np = oracle.params_from_workload, oracle.to_np
+    ws = w.replace(batch=sample_batch)
+    layer = make_layer(ws, seed, 0)
+    p = oracle_params(ws)
+    hk, hv, hb = to_np(layer["host_k"]), to_np(layer["host_v"]), to_np(layer["host_bias"])
+    n_tok = np.full((ws.batch,), ws.context, np.int32)
+    kc, sec = oracle.pool(p, hk, hb, n_tok)
+    B, H, C, nb, d = ws.batch, ws.n_kv_heads, ws.gpu_slots, ws.block_size, ws.head_dim
+    pk, pv = np.zeros((B, H, C, nb, d), hk.dtype), np.zeros((B, H, C, nb, d), hv.dtype)
+    pb = np.zeros((B, H, C, nb), np.float32)
+    sob = np.full((B, H, ws.max_blocks), -1, np.int32)
+    bos = np.full((B, H, C), -1, np.int32)
+    qs = QueryStream(ws, seed, 0)
+
+    def one(t):
+        q = to_np(qs.next(t))
+        sq, se = oracle.block_score(p, q, kc, sec, n_tok)
+        sel, n_sel = oracle.select(p, sq, se, n_tok)
+        ll, n_load = oracle.load(p, sel, n_sel, sob, bos)
+        oracle.fetch(p, hk, hv, hb, pk, pv, pb, ll, n_load)
+        oracle.attention(p, q, pk, pv, pb, sel, n_sel, sob, n_tok)
+
+    one(0)                                   # cold start (fills the pool), untimed
+    t0 = time.perf_counter()
+    for t in range(1, 1 + steps):
+        one(t)
+    dt = time.perf_counter() - t0
+    units = ws.units * steps
+    return {"value": units / dt, "unit": "unit-steps/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{steps} steps of {ws.units} units (batch {sample_batch} of {w.batch}) of the {w.name} workload, "
+                      f"fp64, OpenMP over units, {dt:.1f} s"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the path on ONE GPU (no collectives, no sharding); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2510_13602_amd as nosa
+    from nosa_inputs import CONFIGS, QueryStream, make_layer
+    from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU; the NOSA hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    w = CONFIGS[args.workload]
+    L = args.layers or min(w.layers, 32)
+    LH = max(1, min(args.host_layers, L))
+    t_setup = time.perf_counter()
+
+    params = nosa.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                              k_blocks=w.k_blocks, kq_blocks=w.kq_blocks, sink_blocks=w.sink_blocks,
+                              window_blocks=w.window_blocks, gpu_slots=w.gpu_slots, max_blocks=w.max_blocks,
+                              n_sub_max=w.n_sub_max, dtype=w.dtype)
+    ctx = nosa.Nosa(params, device=dev)
+    if args.splits:
+        ctx.set_splits(args.splits)
+    ctx.set_overlap(not args.no_overlap)
+
+    # host pools: every block of the cache, pinned; drawn on the GPU (seeded) and copied out
+    hosts = []
+    for hl in range(LH):
+        lay = make_layer(w, args.seed, hl, device=dev)
+        hosts.append((pinned_like(lay["host_k"]), pinned_like(lay["host_v"]), pinned_like(lay["host_bias"])))
+        del lay
+        torch.cuda.empty_cache()
+    n_tok = torch.full((w.batch,), w.context, dtype=torch.int32)
+    layers = []
+    for l in range(L):
+        hk, hv, hb = hosts[l % LH]
+        lc = LayerCache(ctx, hk, hv, hb, n_tok)
+        if l < LH:
+            lc.rebuild_pooled()
+        else:                                   # same host pool -> same pooled arrays
+            lc.k_pooled.copy_(layers[l % LH].k_pooled)
+            lc.se_pooled.copy_(layers[l % LH].se_pooled)
+        layers.append(lc)
+    # queries: one stream per host pool (the planted directions belong to the pool)
+    streams = [QueryStream(w, args.seed, hl, device=dev) for hl in range(LH)]
+    total = args.warmup + args.steps
+    n_q = 1 if args.resident else total + L
+    queries = [[streams[hl].next(t) for t in range(n_q)] for hl in range(LH)]
+
+    def q_of(l, i):
+        return queries[l % LH][0 if args.resident else i]
+
+    # cold start of every layer (fills the pool through the real path), then W warm-up steps
+    for l, lc in enumerate(layers):
+        lc.step(q_of(l, 0))
+    torch.cuda.synchronize()
+    cold_loads = float(sum(lc.n_load.float().mean().item() for lc in layers) / L)
+    for i in range(args.warmup):
+        layers[i % L].step(q_of(i % L, 1 + i))
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t_setup
+
+    ctx.timing_enable(True)
+    for k in range(5):
+        ctx.timing_read(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        j = args.warmup + i
+        layers[j % L].step(q_of(j % L, 1 + j))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.timing_enable(False)
+
+    names = ["block_score", "select", "fetch", "sparse_decode", "combine"]
+    kern = {}
+    for k, name in enumerate(names):
+        ms, n = ctx.timing_read(k)
+        kern[name] = {"launches": n, "avg_us": (1e3 * ms / n) if n else None}
+    loads = torch.stack([lc.n_load.float() for lc in layers[:min(L, args.steps)]])
+    mean_load, max_load = float(loads.mean().item()), float(loads.max().item())
+
+    units = w.units
+    dec_us = kern["sparse_decode"]["avg_us"]
+    dec_bytes = decode_bytes_per_unit(w) * units
+    achieved = dec_bytes / (dec_us * 1e-6) / 1e9 if dec_us else None
+    peak = 8000.0
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"sparse_decode_{w.name}_hbm_traffic.json")
+    if os.path.exists(tfile):
+        with open(tfile) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    blk_bytes = 2 * w.block_size * w.head_dim * w.elem_size + w.block_size * 4
+    fetch_us = kern["fetch"]["avg_us"]
+    line = {
+        "metric": "sparse decode steps/sec (batch x KV heads x layer units) at fixed ctx",
+        "value": units * args.steps / dt,
+        "unit": "unit-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * dt / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}-shaped", "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "context": w.context, "block_size": w.block_size, "k_blocks": w.k_blocks,
+                   "kq_blocks": w.kq_blocks, "sink_blocks": w.sink_blocks, "window_blocks": w.window_blocks,
+                   "gpu_slots": w.gpu_slots, "layers_cycled": L, "host_pools": LH, "splits": ctx.splits,
+                   "fetch": "resident (no misses)" if args.resident else ("side stream" if not args.no_overlap else "main stream")},
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel", "achieved": achieved, "peak": peak, "unit": "GB/s",
+                     "frac": (achieved / peak) if achieved else None, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": dec_bytes, "avg_launch_us": dec_us},
+        "cpu_baseline": None,
+        "kernels_avg_us": {k: v["avg_us"] for k, v in kern.items()},
+        "step_hbm_GBps": step_bytes_per_unit(w) * units * args.steps / dt / 1e9,
+        "fetch": {"mean_blocks_per_unit": mean_load, "max_blocks_per_unit": max_load, "cold_start_blocks_per_unit": cold_loads,
+                  "host_link_GBps": (mean_load * units * blk_bytes / (fetch_us * 1e-6) / 1e9) if fetch_us else None},
+        "setup_s": setup_s,
+    }
+    if not args.no_cpu_baseline:
+        for lc in layers:
+            del lc
+        line["cpu_baseline"] = cpu_baseline(w, args.seed, min(args.cpu_sample_batch, w.batch))
+    ctx.close()
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

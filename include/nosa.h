@@ -1,0 +1,179 @@
+/*
+ * libnosa — the decode-step hot path of NOSA (native and offloadable sparse attention) on one
+ * AMD MI355X (gfx950): block score -> constrained block selection -> load positions -> fetch of
+ * offloaded blocks from pinned host memory -> block-sparse attention over the selected blocks.
+ *
+ * Plain C ABI.  No call allocates or frees device memory; every tensor is owned by the caller.
+ * "dev" = device memory, "host" = host memory, "pinned" = page-locked host memory that the GPU
+ * can read (hipHostMalloc).  Unless stated, calls only enqueue work on the context's stream and
+ * return without synchronising; they never read device memory from the host.
+ *
+ * Every call returns NOSA_OK (0) or a negative error code; nothing is launched when argument
+ * validation fails, and no exception or abort crosses this boundary.  nosa_last_error() returns a
+ * description of the last failure on the context (or of the last context-free failure).
+ *
+ * Notation (paper symbol -> field): block size n_b -> block_size; k/n_b -> k_blocks (K);
+ * k_q/n_b -> kq_blocks (Kq); mean-pool kernel / stride l_k, l_s -> pool_kernel, pool_stride;
+ * B batch, Hq query heads, Hkv KV heads, G = Hq/Hkv, d head_dim, T tokens in the cache,
+ * N = ceil(T/n_b) blocks, C GPU slots per (batch, KV head).  A "unit" is one (batch, KV head).
+ *
+ * Tensor layouts (row-major, innermost last):
+ *   q             [B, Hq, d]                 dtype            dev
+ *   k_pooled      [B, Hkv, n_sub_max, d]     dtype            dev   pooled key of sub-block j
+ *   se_pooled     [B, Hkv, n_sub_max]        fp32             dev   pooled importance of sub-block j
+ *   n_tokens      [B]                        int32            dev   T per batch element (counts the current token)
+ *   sq_blk,se_blk [B, Hkv, max_blocks]       fp32             dev   block-level scores, -inf = no score
+ *   sel_idx       [B, Hkv, K]                int32            dev   Gamma(t), ascending, -1 padded
+ *   n_sel         [B, Hkv]                   int32            dev
+ *   slot_of_block [B, Hkv, max_blocks]       int32            dev   GPU slot of a block, -1 = not resident
+ *   block_of_slot [B, Hkv, C]                int32            dev   block held by a slot, -1 = empty
+ *   load_list     [B, Hkv, K, 2]             int32            dev   (block, slot) pairs to fetch, -1 padded
+ *   n_load        [B, Hkv]                   int32            dev
+ *   pool_k,pool_v [B, Hkv, C, n_b, d]        dtype            dev   paged GPU KV pool
+ *   pool_bias     [B, Hkv, C, n_b]           fp32             dev   attention bias b_j of the pooled tokens
+ *   host_k,host_v [B, Hkv, max_blocks, n_b, d] dtype          pinned  every block of the cache
+ *   host_bias     [B, Hkv, max_blocks, n_b]  fp32             pinned
+ *   out           [B, Hq, d]                 dtype            dev
+ *   lse           [B, Hq]                    fp32             dev   natural-log sum of exp of the logits
+ */
+#ifndef NOSA_H
+#define NOSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NOSA_OK 0
+#define NOSA_EINVAL (-1) /* NULL / inconsistent argument, call out of order                      */
+#define NOSA_ESHAPE (-2) /* a shape or budget this build does not support                       */
+#define NOSA_EHIP (-3)   /* a HIP runtime call failed; nosa_last_error() names it               */
+
+#define NOSA_DTYPE_F32 0
+#define NOSA_DTYPE_BF16 1
+
+typedef struct nosa_ctx nosa_ctx; /* opaque: parameters, streams, events, workspace */
+
+/* The hyper-parameter bag of Alg. 1 ("params": k, k_e, k_q, block size, pooling strides) plus the
+ * tensor geometry.  Budget split as in App. B.2: K = sink + window + Kq + Ke, so
+ * Ke = K - sink_blocks - window_blocks - kq_blocks is implied and must be >= 0.               */
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim; /* B, Hq, Hkv, d; d in {64, 128}; Hq % Hkv == 0  */
+  int32_t block_size;                             /* n_b; this build supports 64                   */
+  int32_t pool_kernel, pool_stride;               /* l_k, l_s; both == n_b => one pooled key/block  */
+  int32_t k_blocks, kq_blocks;                    /* K, Kq (Kq bounds the blocks fetched per step)   */
+  int32_t sink_blocks, window_blocks;             /* Ns >= 0, Nw >= 1 (the window holds the tail)    */
+  int32_t gpu_slots;                              /* C >= K                                         */
+  int32_t max_blocks;                             /* capacity of the per-unit block tables          */
+  int32_t n_sub_max;                              /* capacity of k_pooled / se_pooled per unit      */
+  int32_t dtype;                                  /* NOSA_DTYPE_F32 or NOSA_DTYPE_BF16 (q, K, V, out) */
+  float softmax_scale;                            /* multiplies q.k only; <= 0 selects 1/sqrt(d)     */
+} nosa_params;
+
+/* ---- context ---------------------------------------------------------------------------------*/
+
+/* Pure host check of a parameter set (no GPU needed).  Returns NOSA_OK, NOSA_EINVAL or NOSA_ESHAPE;
+ * when msg != NULL a description of the first problem is copied into it (at most msg_len bytes). */
+int nosa_validate_params(const nosa_params* p, char* msg, size_t msg_len);
+
+/* Creates a context for one layer shape.  main_stream is a hipStream_t (NULL = the default
+ * stream) on which score, select and decode are enqueued; the context creates one more stream of
+ * default priority for fetches, and the events that order the two.  The current device at the
+ * time of the call is the context's device.                                                      */
+int nosa_create(nosa_ctx** out, const nosa_params* p, void* main_stream);
+int nosa_destroy(nosa_ctx* ctx); /* synchronises both streams, destroys them; frees no caller memory */
+
+/* Scratch for the split partial results of nosa_sparse_decode.  The caller allocates
+ * nosa_workspace_bytes() bytes of device memory (256-byte aligned) and hands them over once; the
+ * buffer must stay valid until nosa_destroy.                                                     */
+size_t nosa_workspace_bytes(const nosa_params* p);
+int nosa_set_workspace(nosa_ctx* ctx, void* dev_ws, size_t bytes);
+
+/* Number of partial results per unit in nosa_sparse_decode (1..NOSA_MAX_SPLITS); the default is
+ * chosen from the shape.  The workspace is sized for NOSA_MAX_SPLITS.                            */
+#define NOSA_MAX_SPLITS 16
+int nosa_set_splits(nosa_ctx* ctx, int splits);
+int nosa_get_splits(const nosa_ctx* ctx);
+
+/* overlap = 1 (default): fetches run on the context's own stream and the attention over the
+ * blocks that were already resident does not wait for them.  overlap = 0: everything is enqueued
+ * on the main stream in call order (used to check that both orders give the same bits).          */
+int nosa_set_overlap(nosa_ctx* ctx, int overlap);
+
+const char* nosa_last_error(const nosa_ctx* ctx); /* ctx may be NULL */
+
+/* ---- the hot path (Alg. 1, one decode step of one layer) -------------------------------------*/
+
+/* Stage 1, scores.  S_c^q = Q K_c^T (Sec. 2.1), summed over the G query heads of each KV head,
+ * then the block-level max over the sub-blocks that lie wholly inside a block, applied
+ * identically to the query-aware score and to the pooled importance score (mean-pooling and
+ * max-pooling Eqs. of Sec. 3.1; "fused_pooling" in Alg. 1).  Sub-block j covers tokens
+ * [j*l_s, j*l_s + l_k) and exists once all its tokens do.  Raw dot products: no scale, no softmax.
+ * Writes sq_blk and se_blk for every block index < max_blocks (-inf where a block has no complete
+ * sub-block).  All pointers dev.                                                                 */
+int nosa_block_score(nosa_ctx* ctx, const void* q, const void* k_pooled, const float* se_pooled,
+                     const int32_t* n_tokens, float* sq_blk, float* se_blk);
+
+/* Stage 1, selection, and the load positions.
+ * Selection (selection Eq. of Sec. 3.1; Alg. 1 select_topk_indices): sink blocks and the last
+ * window_blocks blocks are forced (InfLLMv2 mask, Sec. 2.1); among the remaining complete blocks
+ * the Kq best by sq_blk are taken, then the Ke best of the rest by se_blk; ties go to the lower
+ * block index.  sel_idx receives Gamma(t) in ascending order.
+ * Load positions (Sec. 4 "Memory Layout and Block Selection"; Alg. 1 generate_load_positions):
+ * the selected blocks without a slot, in ascending order, are paired with the slots (ascending)
+ * that are empty or hold a block outside Gamma(t); both residency maps are updated in place and
+ * the pairs are written to load_list / n_load.  With C == K and an unchanged cache, n_load <= Kq
+ * on every step after the first (Theorem 1).  All pointers dev; nothing is read back.            */
+int nosa_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const int32_t* n_tokens,
+                int32_t* sel_idx, int32_t* n_sel, int32_t* slot_of_block, int32_t* block_of_slot,
+                int32_t* load_list, int32_t* n_load);
+
+/* Host-to-device transfer of the missed blocks (Sec. 4 "Offloading Communication"; Alg. 1
+ * host_to_device_communication): a gather kernel reads each listed block's keys, values and bias
+ * straight from pinned host memory and writes them into the block's slot.  host_* are pinned host
+ * pointers (host_bias and pool_bias may both be NULL); pool_*, load_list, n_load are dev.
+ * Ordered after the preceding nosa_select and before the following nosa_sparse_decode.           */
+int nosa_fetch(nosa_ctx* ctx, const void* host_k, const void* host_v, const float* host_bias,
+               void* pool_k, void* pool_v, float* pool_bias, const int32_t* load_list,
+               const int32_t* n_load);
+
+/* Stage 2, attention (output Eq. of Sec. 3.1 "Attention Calculation"): for every query head,
+ * softmax over the tokens j < T of the selected blocks of  softmax_scale * q.k_j + b_j, times V;
+ * exp(b_j) exp(q k_j + m_j) of the paper is the same thing with the mask m_j realised by visiting
+ * only selected blocks.  pool_bias may be NULL (b = 0); lse may be NULL.  Every selected block
+ * must have a slot (nosa_select guarantees it).  All pointers dev.                               */
+int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v,
+                       const float* pool_bias, const int32_t* sel_idx, const int32_t* n_sel,
+                       const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse);
+
+/* ---- cache maintenance (Alg. 1 update_compressed_k / update_importance_score) ----------------*/
+
+/* Rebuilds k_pooled and se_pooled from a whole cache: K_c[j] = mean of the keys of sub-block j
+ * (block compression f_c, Sec. 2.1), S_c^e[j] = mean of the importance score b over it (mean-pooling
+ * Eq.).  keys [B,Hkv,max_blocks,n_b,d] and bias [B,Hkv,max_blocks,n_b] may be dev or pinned host
+ * memory.  Accumulates in fp32, rounds K_c to dtype (nearest even).  Sub-blocks not complete at
+ * n_tokens are written as zero.  Not part of the timed path.                                    */
+int nosa_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const int32_t* n_tokens,
+                     void* k_pooled, float* se_pooled);
+
+/* ---- per-kernel timing for benchmarks --------------------------------------------------------*/
+
+#define NOSA_KERNEL_SCORE 0
+#define NOSA_KERNEL_SELECT 1
+#define NOSA_KERNEL_FETCH 2
+#define NOSA_KERNEL_DECODE 3  /* the split attention kernel (dominant) */
+#define NOSA_KERNEL_COMBINE 4
+#define NOSA_KERNEL_COUNT 5
+/* When enabled, each launch of the kernels above is bracketed by HIP events on the stream it runs
+ * on.  nosa_timing_read synchronises those events, returns the summed duration and the number of
+ * launches since the last read, and resets the counters.  At most 4096 launches per kernel are
+ * kept between reads.                                                                           */
+int nosa_timing_enable(nosa_ctx* ctx, int on);
+int nosa_timing_read(nosa_ctx* ctx, int kernel, double* total_ms, int32_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NOSA_H */

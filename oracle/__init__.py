@@ -210,3 +210,26 @@ def attention(p: Params, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_b
     if bad:
         raise RuntimeError(f"oracle_attention: {bad} selected blocks have no slot")
     return (out, lse, probs) if with_probs else (out, lse)
+
+
+# ---- conveniences for callers that hold torch tensors / workload descriptions -------------------
+
+def to_np(t) -> np.ndarray:
+    """torch tensor -> numpy on the host; bf16 travels as uint16 bit patterns."""
+    import torch
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+def params_from_workload(w, **over) -> Params:
+    """Oracle parameters of a workload description (any object with the shape attributes)."""
+    kw = dict(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+              k_blocks=w.k_blocks, kq_blocks=w.kq_blocks, sink_blocks=w.sink_blocks,
+              window_blocks=w.window_blocks, gpu_slots=w.gpu_slots, max_blocks=w.max_blocks,
+              n_sub_max=w.n_sub_max, dtype=0 if w.dtype == "fp32" else 1,
+              softmax_scale=1.0 / float(w.head_dim) ** 0.5, block_size=w.block_size,
+              pool_kernel=w.pool_kernel, pool_stride=w.pool_stride)
+    kw.update(over)
+    return Params(**kw)

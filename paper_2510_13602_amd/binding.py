@@ -1,0 +1,244 @@
+"""Thin ctypes binding of libnosa.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in include/nosa.h;
+PyTorch tensors are used here for device / pinned memory and for the stream handle, nothing else.
+There is no CPU fallback: if the library is missing or no GPU is present, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnosa.so")
+
+NOSA_OK, NOSA_EINVAL, NOSA_ESHAPE, NOSA_EHIP = 0, -1, -2, -3
+DTYPE_F32, DTYPE_BF16 = 0, 1
+KERNEL_SCORE, KERNEL_SELECT, KERNEL_FETCH, KERNEL_DECODE, KERNEL_COMBINE = range(5)
+MAX_SPLITS = 16
+
+EXPORTS = [
+    "nosa_validate_params", "nosa_create", "nosa_destroy", "nosa_workspace_bytes", "nosa_set_workspace",
+    "nosa_set_splits", "nosa_get_splits", "nosa_set_overlap", "nosa_last_error", "nosa_block_score",
+    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_timing_enable",
+    "nosa_timing_read",
+]
+
+
+class NosaError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libnosa error {code}: {msg}")
+        self.code = code
+
+
+class Params(ctypes.Structure):
+    """Mirror of ``nosa_params`` (include/nosa.h)."""
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "batch", "n_q_heads", "n_kv_heads", "head_dim", "block_size", "pool_kernel", "pool_stride",
+        "k_blocks", "kq_blocks", "sink_blocks", "window_blocks", "gpu_slots", "max_blocks", "n_sub_max",
+        "dtype")] + [("softmax_scale", ctypes.c_float)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the in-tree libnosa.so; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no CPU fallback for the NOSA hot path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32p, fp = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+    lib.nosa_validate_params.argtypes = [ctypes.POINTER(Params), ctypes.c_char_p, ctypes.c_size_t]
+    lib.nosa_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(Params), vp]
+    lib.nosa_destroy.argtypes = [vp]
+    lib.nosa_workspace_bytes.argtypes = [ctypes.POINTER(Params)]
+    lib.nosa_workspace_bytes.restype = ctypes.c_size_t
+    lib.nosa_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
+    lib.nosa_set_splits.argtypes = [vp, ctypes.c_int]
+    lib.nosa_get_splits.argtypes = [vp]
+    lib.nosa_set_overlap.argtypes = [vp, ctypes.c_int]
+    lib.nosa_last_error.argtypes = [vp]
+    lib.nosa_last_error.restype = ctypes.c_char_p
+    lib.nosa_block_score.argtypes = [vp, vp, vp, fp, i32p, fp, fp]
+    lib.nosa_select.argtypes = [vp, fp, fp, i32p, i32p, i32p, i32p, i32p, i32p, i32p]
+    lib.nosa_fetch.argtypes = [vp, vp, vp, fp, vp, vp, fp, i32p, i32p]
+    lib.nosa_sparse_decode.argtypes = [vp, vp, vp, vp, fp, i32p, i32p, i32p, i32p, vp, fp]
+    lib.nosa_pool_blocks.argtypes = [vp, vp, fp, i32p, vp, fp]
+    lib.nosa_timing_enable.argtypes = [vp, ctypes.c_int]
+    lib.nosa_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
+    for name in EXPORTS:
+        if name not in ("nosa_workspace_bytes", "nosa_last_error"):
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def make_params(*, batch, n_q_heads, n_kv_heads, head_dim, k_blocks, kq_blocks, sink_blocks, window_blocks,
+                gpu_slots, max_blocks, n_sub_max, dtype, softmax_scale=0.0, block_size=64, pool_kernel=64,
+                pool_stride=64) -> Params:
+    if isinstance(dtype, torch.dtype):
+        dtype = {torch.float32: DTYPE_F32, torch.bfloat16: DTYPE_BF16}[dtype]
+    elif isinstance(dtype, str):
+        dtype = {"fp32": DTYPE_F32, "bf16": DTYPE_BF16}[dtype]
+    return Params(batch, n_q_heads, n_kv_heads, head_dim, block_size, pool_kernel, pool_stride, k_blocks,
+                  kq_blocks, sink_blocks, window_blocks, gpu_slots, max_blocks, n_sub_max, dtype,
+                  float(softmax_scale))
+
+
+def validate_params(p: Params) -> None:
+    buf = ctypes.create_string_buffer(256)
+    rc = load_library().nosa_validate_params(ctypes.byref(p), buf, 256)
+    if rc != NOSA_OK:
+        raise NosaError(rc, buf.value.decode())
+
+
+def _dev(t: Optional[torch.Tensor], dtype, shape, name: str):
+    """Device tensor -> raw pointer, after checking dtype / shape / contiguity."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    return _raw(t, dtype, shape, name)
+
+
+def _raw(t: torch.Tensor, dtype, shape, name: str):
+    if t.dtype != dtype:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Nosa:
+    """One context = one layer shape (see ``nosa_create``).  Methods mirror the C entry points."""
+
+    def __init__(self, params: Params, stream: Optional[torch.cuda.Stream] = None, device="cuda:0"):
+        self.lib = load_library()
+        if not torch.cuda.is_available():
+            raise NosaError(NOSA_EHIP, "no GPU: the NOSA hot path has no CPU fallback")
+        self.p = params
+        self.device = torch.device(device)
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        self._ctx = ctypes.c_void_p()
+        with torch.cuda.device(self.device):
+            rc = self.lib.nosa_create(ctypes.byref(self._ctx), ctypes.byref(params), ctypes.c_void_p(self.stream.cuda_stream))
+        if rc != NOSA_OK:
+            raise NosaError(rc, self.lib.nosa_last_error(None).decode())
+        nbytes = self.lib.nosa_workspace_bytes(ctypes.byref(params))
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self._check(self.lib.nosa_set_workspace(self._ctx, ctypes.c_void_p(self.workspace.data_ptr()), nbytes))
+        self.tdtype = torch.float32 if params.dtype == DTYPE_F32 else torch.bfloat16
+
+    # -- plumbing ------------------------------------------------------------------------------
+    def _check(self, rc: int) -> None:
+        if rc != NOSA_OK:
+            raise NosaError(rc, self.lib.nosa_last_error(self._ctx).decode())
+
+    def close(self) -> None:
+        if self._ctx:
+            self.lib.nosa_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def splits(self) -> int:
+        return self.lib.nosa_get_splits(self._ctx)
+
+    def set_splits(self, s: int) -> None:
+        self._check(self.lib.nosa_set_splits(self._ctx, s))
+
+    def set_overlap(self, on: bool) -> None:
+        self._check(self.lib.nosa_set_overlap(self._ctx, 1 if on else 0))
+
+    def timing_enable(self, on: bool) -> None:
+        self._check(self.lib.nosa_timing_enable(self._ctx, 1 if on else 0))
+
+    def timing_read(self, kernel: int):
+        ms, n = ctypes.c_double(), ctypes.c_int32()
+        self._check(self.lib.nosa_timing_read(self._ctx, kernel, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
+
+    # -- shapes --------------------------------------------------------------------------------
+    @property
+    def _B(self): return self.p.batch
+    @property
+    def _H(self): return self.p.n_kv_heads
+
+    # -- the calls -----------------------------------------------------------------------------
+    def nosa_block_score(self, q, k_pooled, se_pooled, n_tokens, sq_blk, se_blk) -> None:
+        p, B, H = self.p, self._B, self._H
+        self._check(self.lib.nosa_block_score(
+            self._ctx, _dev(q, self.tdtype, (B, p.n_q_heads, p.head_dim), "q"),
+            _dev(k_pooled, self.tdtype, (B, H, p.n_sub_max, p.head_dim), "k_pooled"),
+            _dev(se_pooled, torch.float32, (B, H, p.n_sub_max), "se_pooled"),
+            _dev(n_tokens, torch.int32, (B,), "n_tokens"),
+            _dev(sq_blk, torch.float32, (B, H, p.max_blocks), "sq_blk"),
+            _dev(se_blk, torch.float32, (B, H, p.max_blocks), "se_blk")))
+
+    def nosa_select(self, sq_blk, se_blk, n_tokens, sel_idx, n_sel, slot_of_block, block_of_slot, load_list, n_load) -> None:
+        p, B, H = self.p, self._B, self._H
+        self._check(self.lib.nosa_select(
+            self._ctx, _dev(sq_blk, torch.float32, (B, H, p.max_blocks), "sq_blk"),
+            _dev(se_blk, torch.float32, (B, H, p.max_blocks), "se_blk"),
+            _dev(n_tokens, torch.int32, (B,), "n_tokens"),
+            _dev(sel_idx, torch.int32, (B, H, p.k_blocks), "sel_idx"),
+            _dev(n_sel, torch.int32, (B, H), "n_sel"),
+            _dev(slot_of_block, torch.int32, (B, H, p.max_blocks), "slot_of_block"),
+            _dev(block_of_slot, torch.int32, (B, H, p.gpu_slots), "block_of_slot"),
+            _dev(load_list, torch.int32, (B, H, p.k_blocks, 2), "load_list"),
+            _dev(n_load, torch.int32, (B, H), "n_load")))
+
+    def nosa_fetch(self, host_k, host_v, host_bias, pool_k, pool_v, pool_bias, load_list, n_load) -> None:
+        p, B, H = self.p, self._B, self._H
+        kv_host = (B, H, p.max_blocks, p.block_size, p.head_dim)
+        kv_pool = (B, H, p.gpu_slots, p.block_size, p.head_dim)
+        for t, name in ((host_k, "host_k"), (host_v, "host_v"), (host_bias, "host_bias")):
+            if t is not None and not (t.is_cuda or t.is_pinned()):
+                raise ValueError(f"{name} must be pinned host memory (or device memory)")
+        self._check(self.lib.nosa_fetch(
+            self._ctx, _raw(host_k, self.tdtype, kv_host, "host_k"), _raw(host_v, self.tdtype, kv_host, "host_v"),
+            None if host_bias is None else _raw(host_bias, torch.float32, kv_host[:4], "host_bias"),
+            _dev(pool_k, self.tdtype, kv_pool, "pool_k"), _dev(pool_v, self.tdtype, kv_pool, "pool_v"),
+            _dev(pool_bias, torch.float32, kv_pool[:4], "pool_bias"),
+            _dev(load_list, torch.int32, (B, H, p.k_blocks, 2), "load_list"),
+            _dev(n_load, torch.int32, (B, H), "n_load")))
+
+    def nosa_sparse_decode(self, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse=None) -> None:
+        p, B, H = self.p, self._B, self._H
+        kv_pool = (B, H, p.gpu_slots, p.block_size, p.head_dim)
+        self._check(self.lib.nosa_sparse_decode(
+            self._ctx, _dev(q, self.tdtype, (B, p.n_q_heads, p.head_dim), "q"),
+            _dev(pool_k, self.tdtype, kv_pool, "pool_k"), _dev(pool_v, self.tdtype, kv_pool, "pool_v"),
+            _dev(pool_bias, torch.float32, kv_pool[:4], "pool_bias"),
+            _dev(sel_idx, torch.int32, (B, H, p.k_blocks), "sel_idx"),
+            _dev(n_sel, torch.int32, (B, H), "n_sel"),
+            _dev(slot_of_block, torch.int32, (B, H, p.max_blocks), "slot_of_block"),
+            _dev(n_tokens, torch.int32, (B,), "n_tokens"),
+            _dev(out, self.tdtype, (B, p.n_q_heads, p.head_dim), "out"),
+            _dev(lse, torch.float32, (B, p.n_q_heads), "lse")))
+
+    def nosa_pool_blocks(self, keys, bias, n_tokens, k_pooled, se_pooled) -> None:
+        p, B, H = self.p, self._B, self._H
+        kv = (B, H, p.max_blocks, p.block_size, p.head_dim)
+        for t, name in ((keys, "keys"), (bias, "bias")):
+            if not (t.is_cuda or t.is_pinned()):
+                raise ValueError(f"{name} must be device or pinned host memory")
+        self._check(self.lib.nosa_pool_blocks(
+            self._ctx, _raw(keys, self.tdtype, kv, "keys"), _raw(bias, torch.float32, kv[:4], "bias"),
+            _dev(n_tokens, torch.int32, (B,), "n_tokens"),
+            _dev(k_pooled, self.tdtype, (B, H, p.n_sub_max, p.head_dim), "k_pooled"),
+            _dev(se_pooled, torch.float32, (B, H, p.n_sub_max), "se_pooled")))

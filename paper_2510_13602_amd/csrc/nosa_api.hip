@@ -1,0 +1,304 @@
+// C-ABI entry points of libnosa: argument validation, context, stream ordering, timing.
+// Every entry point validates before it launches; the kernels live in the other files.
+#include <cmath>
+#include <new>
+
+#include "nosa_internal.h"
+
+namespace {
+thread_local char g_err[512] = {0};  // errors raised without a context
+}
+
+namespace nosa {
+
+int set_error(nosa_ctx* ctx, int code, const char* fmt, ...) {
+  char* dst = ctx ? ctx->err : g_err;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, 512, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+TimedLaunch::TimedLaunch(nosa_ctx* c, int k, hipStream_t s) : ctx(c), kernel(k), stream(s) {
+  if (!ctx->timing) return;
+  Timing& t = ctx->timed[kernel];
+  if (t.n >= kMaxTimed) return;
+  if (!t.start[t.n]) {
+    if (hipEventCreate(&t.start[t.n]) != hipSuccess || hipEventCreate(&t.stop[t.n]) != hipSuccess) return;
+  }
+  slot = t.n;
+  (void)hipEventRecord(t.start[slot], stream);
+}
+
+TimedLaunch::~TimedLaunch() {
+  if (slot < 0) return;
+  Timing& t = ctx->timed[kernel];
+  (void)hipEventRecord(t.stop[slot], stream);
+  t.n = slot + 1;
+}
+
+}  // namespace nosa
+
+using nosa::set_error;
+
+static int failf(char* msg, size_t len, int code, const char* fmt, ...) __attribute__((format(printf, 4, 5)));
+static int failf(char* msg, size_t len, int code, const char* fmt, ...) {
+  if (msg && len) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(msg, len, fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+static int validate(const nosa_params* p, char* msg, size_t len) {
+#define fail(...) failf(msg, len, __VA_ARGS__)
+  if (!p) return fail(NOSA_EINVAL, "params is NULL");
+  if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1)
+    return fail(NOSA_EINVAL, "batch, n_q_heads, n_kv_heads must be >= 1 (got %d, %d, %d)", p->batch,
+                p->n_q_heads, p->n_kv_heads);
+  if (p->n_q_heads % p->n_kv_heads != 0)
+    return fail(NOSA_EINVAL, "n_q_heads (%d) must be a multiple of n_kv_heads (%d)", p->n_q_heads, p->n_kv_heads);
+  if (p->dtype != NOSA_DTYPE_F32 && p->dtype != NOSA_DTYPE_BF16) return fail(NOSA_EINVAL, "unknown dtype %d", p->dtype);
+  if (p->head_dim != 64 && p->head_dim != 128) return fail(NOSA_ESHAPE, "head_dim %d not in {64, 128}", p->head_dim);
+  if (p->block_size != nosa::kBlockTokens) return fail(NOSA_ESHAPE, "block_size %d unsupported (64 only)", p->block_size);
+  if (!nosa::decode_supports_group(p->n_q_heads / p->n_kv_heads))
+    return fail(NOSA_ESHAPE, "GQA group %d unsupported (1, 2, 3, 4, 6, 8, 12, 16)", p->n_q_heads / p->n_kv_heads);
+  if (p->pool_kernel < 1 || p->pool_stride < 1 || p->pool_kernel > p->block_size)
+    return fail(NOSA_EINVAL, "pool_kernel (%d) must be in [1, block_size], pool_stride (%d) >= 1", p->pool_kernel,
+                p->pool_stride);
+  if (p->k_blocks < 1 || p->kq_blocks < 0 || p->sink_blocks < 0 || p->window_blocks < 1)
+    return fail(NOSA_EINVAL, "need k_blocks >= 1, kq_blocks >= 0, sink_blocks >= 0, window_blocks >= 1");
+  if (p->sink_blocks + p->window_blocks + p->kq_blocks > p->k_blocks)
+    return fail(NOSA_ESHAPE, "budget: sink (%d) + window (%d) + kq (%d) exceeds k_blocks (%d)", p->sink_blocks,
+                p->window_blocks, p->kq_blocks, p->k_blocks);
+  if (p->k_blocks > nosa::kMaxSelBlocks) return fail(NOSA_ESHAPE, "k_blocks %d > %d", p->k_blocks, nosa::kMaxSelBlocks);
+  if (p->gpu_slots < p->k_blocks) return fail(NOSA_ESHAPE, "gpu_slots (%d) < k_blocks (%d)", p->gpu_slots, p->k_blocks);
+  if (p->max_blocks < 1 || p->max_blocks > nosa::kMaxSelectBlocks)
+    return fail(NOSA_ESHAPE, "max_blocks %d not in [1, %d]", p->max_blocks, nosa::kMaxSelectBlocks);
+  if (p->n_sub_max < 0) return fail(NOSA_EINVAL, "n_sub_max < 0");
+  {
+    // every sub-block index that can be complete within max_blocks must fit the pooled arrays
+    const long long tmax = 1LL * p->max_blocks * p->block_size;
+    const long long need = tmax < p->pool_kernel ? 0 : (tmax - p->pool_kernel) / p->pool_stride + 1;
+    if (p->n_sub_max > need) return fail(NOSA_EINVAL, "n_sub_max %d exceeds the %lld sub-blocks of max_blocks", p->n_sub_max, need);
+  }
+  if (!(p->softmax_scale == p->softmax_scale) || std::isinf(p->softmax_scale)) return fail(NOSA_EINVAL, "softmax_scale is not finite");
+  if (msg && len) msg[0] = 0;
+  return NOSA_OK;
+#undef fail
+}
+
+extern "C" {
+
+int nosa_validate_params(const nosa_params* p, char* msg, size_t msg_len) { return validate(p, msg, msg_len); }
+
+const char* nosa_last_error(const nosa_ctx* ctx) { return ctx ? ctx->err : g_err; }
+
+size_t nosa_workspace_bytes(const nosa_params* p) {
+  if (validate(p, nullptr, 0) != NOSA_OK) return 0;
+  const size_t units = (size_t)p->batch * p->n_kv_heads;
+  const size_t g = p->n_q_heads / p->n_kv_heads;
+  // two partitions (resident, fetched) x NOSA_MAX_SPLITS partial results per unit: O[g][d], (m, l)[g]
+  const size_t per_part = g * (size_t)(p->head_dim + 2) * sizeof(float);
+  return units * 2 * NOSA_MAX_SPLITS * per_part + 256;
+}
+
+int nosa_create(nosa_ctx** out, const nosa_params* p, void* main_stream) {
+  if (!out) return set_error(nullptr, NOSA_EINVAL, "out is NULL");
+  *out = nullptr;
+  char msg[256];
+  int rc = validate(p, msg, sizeof msg);
+  if (rc != NOSA_OK) return set_error(nullptr, rc, "%s", msg);
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1)
+    return set_error(nullptr, NOSA_EHIP, "no HIP device available: libnosa has no CPU fallback");
+  nosa_ctx* ctx = new (std::nothrow) nosa_ctx();
+  if (!ctx) return set_error(nullptr, NOSA_EINVAL, "out of host memory");
+  ctx->p = *p;
+  ctx->group = p->n_q_heads / p->n_kv_heads;
+  ctx->units = p->batch * p->n_kv_heads;
+  ctx->scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
+  ctx->main = (hipStream_t)main_stream;
+  ctx->splits = nosa::decode_default_splits(*p);
+  auto bail = [&](const char* what, hipError_t e) {
+    set_error(nullptr, NOSA_EHIP, "%s failed: %s", what, hipGetErrorString(e));
+    nosa_destroy(ctx);
+    return NOSA_EHIP;
+  };
+  hipError_t e;
+  if ((e = hipGetDevice(&ctx->device)) != hipSuccess) return bail("hipGetDevice", e);
+  if ((e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking)) != hipSuccess) return bail("hipStreamCreateWithFlags", e);
+  if ((e = hipEventCreateWithFlags(&ctx->ev_select, hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+  if ((e = hipEventCreateWithFlags(&ctx->ev_fetch, hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+  for (int k = 0; k < NOSA_KERNEL_COUNT; ++k) {
+    ctx->timed[k].start = new (std::nothrow) hipEvent_t[nosa::kMaxTimed]();
+    ctx->timed[k].stop = new (std::nothrow) hipEvent_t[nosa::kMaxTimed]();
+    if (!ctx->timed[k].start || !ctx->timed[k].stop) {
+      nosa_destroy(ctx);
+      return set_error(nullptr, NOSA_EINVAL, "out of host memory");
+    }
+  }
+  *out = ctx;
+  return NOSA_OK;
+}
+
+int nosa_destroy(nosa_ctx* ctx) {
+  if (!ctx) return NOSA_OK;
+  if (ctx->side) (void)hipStreamSynchronize(ctx->side);
+  (void)hipStreamSynchronize(ctx->main);
+  for (int k = 0; k < NOSA_KERNEL_COUNT; ++k) {
+    nosa::Timing& t = ctx->timed[k];
+    for (int i = 0; i < nosa::kMaxTimed; ++i) {
+      if (t.start && t.start[i]) (void)hipEventDestroy(t.start[i]);
+      if (t.stop && t.stop[i]) (void)hipEventDestroy(t.stop[i]);
+    }
+    delete[] t.start;
+    delete[] t.stop;
+  }
+  if (ctx->ev_select) (void)hipEventDestroy(ctx->ev_select);
+  if (ctx->ev_fetch) (void)hipEventDestroy(ctx->ev_fetch);
+  if (ctx->side) (void)hipStreamDestroy(ctx->side);
+  delete ctx;
+  return NOSA_OK;
+}
+
+int nosa_set_workspace(nosa_ctx* ctx, void* dev_ws, size_t bytes) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, dev_ws, NOSA_EINVAL, "workspace is NULL");
+  NOSA_REQUIRE(ctx, ((uintptr_t)dev_ws & 255) == 0, NOSA_EINVAL, "workspace must be 256-byte aligned");
+  NOSA_REQUIRE(ctx, bytes >= nosa_workspace_bytes(&ctx->p), NOSA_EINVAL, "workspace too small: %zu < %zu", bytes,
+               nosa_workspace_bytes(&ctx->p));
+  ctx->ws = dev_ws;
+  ctx->ws_bytes = bytes;
+  return NOSA_OK;
+}
+
+int nosa_set_splits(nosa_ctx* ctx, int splits) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, splits >= 1 && splits <= NOSA_MAX_SPLITS, NOSA_EINVAL, "splits %d not in [1, %d]", splits, NOSA_MAX_SPLITS);
+  ctx->splits = splits;
+  return NOSA_OK;
+}
+
+int nosa_get_splits(const nosa_ctx* ctx) { return ctx ? ctx->splits : NOSA_EINVAL; }
+
+int nosa_set_overlap(nosa_ctx* ctx, int overlap) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  // a fetch in flight on the side stream must land before the ordering model changes
+  if (ctx->fetch_pending) {
+    NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, ctx->ev_fetch, 0));
+    ctx->fetch_pending = false;
+  }
+  ctx->overlap = overlap ? 1 : 0;
+  return NOSA_OK;
+}
+
+int nosa_block_score(nosa_ctx* ctx, const void* q, const void* k_pooled, const float* se_pooled,
+                     const int32_t* n_tokens, float* sq_blk, float* se_blk) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, q && n_tokens && sq_blk && se_blk, NOSA_EINVAL, "nosa_block_score: NULL argument");
+  NOSA_REQUIRE(ctx, ctx->p.n_sub_max == 0 || (k_pooled && se_pooled), NOSA_EINVAL,
+               "nosa_block_score: k_pooled / se_pooled is NULL");
+  return nosa::launch_block_score(ctx, q, k_pooled, se_pooled, n_tokens, sq_blk, se_blk);
+}
+
+int nosa_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const int32_t* n_tokens,
+                int32_t* sel_idx, int32_t* n_sel, int32_t* slot_of_block, int32_t* block_of_slot,
+                int32_t* load_list, int32_t* n_load) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, sq_blk && se_blk && n_tokens && sel_idx && n_sel && slot_of_block && block_of_slot && load_list && n_load,
+               NOSA_EINVAL, "nosa_select: NULL argument");
+  // The maps and the pool slots they describe may still be read by the previous step's fetch.
+  if (ctx->fetch_pending) {
+    NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, ctx->ev_fetch, 0));
+    ctx->fetch_pending = false;
+  }
+  int rc = nosa::launch_select(ctx, sq_blk, se_blk, n_tokens, sel_idx, n_sel, slot_of_block, block_of_slot, load_list, n_load);
+  if (rc != NOSA_OK) return rc;
+  NOSA_HIP(ctx, hipEventRecord(ctx->ev_select, ctx->main));
+  ctx->select_recorded = true;
+  return NOSA_OK;
+}
+
+int nosa_fetch(nosa_ctx* ctx, const void* host_k, const void* host_v, const float* host_bias,
+               void* pool_k, void* pool_v, float* pool_bias, const int32_t* load_list, const int32_t* n_load) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, host_k && host_v && pool_k && pool_v && load_list && n_load, NOSA_EINVAL, "nosa_fetch: NULL argument");
+  NOSA_REQUIRE(ctx, (host_bias == nullptr) == (pool_bias == nullptr), NOSA_EINVAL,
+               "nosa_fetch: host_bias and pool_bias must both be given or both be NULL");
+  // The gather kernel dereferences the host pointers on the GPU: they must be page-locked and mapped.
+  const void* hp[3] = {host_k, host_v, host_bias};
+  for (int i = 0; i < 3; ++i) {
+    if (!hp[i]) continue;
+    hipPointerAttribute_t at;
+    hipError_t e = hipPointerGetAttributes(&at, hp[i]);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      return set_error(ctx, NOSA_EINVAL, "nosa_fetch: host pointer %d is not known to HIP (must be pinned or device memory)", i);
+    }
+    NOSA_REQUIRE(ctx, at.type == hipMemoryTypeHost || at.type == hipMemoryTypeDevice || at.type == hipMemoryTypeManaged,
+                 NOSA_EINVAL, "nosa_fetch: host pointer %d is pageable host memory", i);
+  }
+  hipStream_t s = ctx->main;
+  if (ctx->overlap) {
+    NOSA_REQUIRE(ctx, ctx->select_recorded, NOSA_EINVAL, "nosa_fetch called before any nosa_select");
+    NOSA_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_select, 0));
+    s = ctx->side;
+  }
+  int rc = nosa::launch_fetch(ctx, s, host_k, host_v, host_bias, pool_k, pool_v, pool_bias, load_list, n_load);
+  if (rc != NOSA_OK) return rc;
+  if (ctx->overlap) {
+    NOSA_HIP(ctx, hipEventRecord(ctx->ev_fetch, ctx->side));
+    ctx->fetch_pending = true;
+  }
+  return NOSA_OK;
+}
+
+int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v,
+                       const float* pool_bias, const int32_t* sel_idx, const int32_t* n_sel,
+                       const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, q && pool_k && pool_v && sel_idx && n_sel && slot_of_block && n_tokens && out, NOSA_EINVAL,
+               "nosa_sparse_decode: NULL argument");
+  NOSA_REQUIRE(ctx, ctx->splits == 1 || ctx->ws, NOSA_EINVAL, "nosa_sparse_decode: no workspace set (nosa_set_workspace)");
+  if (ctx->fetch_pending) {
+    NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, ctx->ev_fetch, 0));
+    ctx->fetch_pending = false;
+  }
+  return nosa::launch_decode(ctx, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse);
+}
+
+int nosa_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const int32_t* n_tokens,
+                     void* k_pooled, float* se_pooled) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, keys && bias && n_tokens && k_pooled && se_pooled, NOSA_EINVAL, "nosa_pool_blocks: NULL argument");
+  return nosa::launch_pool_blocks(ctx, keys, bias, n_tokens, k_pooled, se_pooled);
+}
+
+int nosa_timing_enable(nosa_ctx* ctx, int on) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  ctx->timing = on != 0;
+  return NOSA_OK;
+}
+
+int nosa_timing_read(nosa_ctx* ctx, int kernel, double* total_ms, int32_t* launches) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, kernel >= 0 && kernel < NOSA_KERNEL_COUNT && total_ms && launches, NOSA_EINVAL, "nosa_timing_read: bad argument");
+  nosa::Timing& t = ctx->timed[kernel];
+  double sum = 0.0;
+  for (int i = 0; i < t.n; ++i) {
+    NOSA_HIP(ctx, hipEventSynchronize(t.stop[i]));
+    float ms = 0.f;
+    NOSA_HIP(ctx, hipEventElapsedTime(&ms, t.start[i], t.stop[i]));
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = t.n;
+  t.n = 0;
+  return NOSA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,434 @@
+// Block-sparse decode attention over the selected blocks of the paged GPU pool
+// (output Eq. of Sec. 3.1 "Attention Calculation"; Alg. 1 Stage 2), as split partial results
+// plus a combine pass.
+//
+// The work is a stream over K and V rows (4 flop per byte): it is HBM-bound, so the kernel is
+// organised around wide coalesced loads, not around matrix cores.
+//
+// Mapping.  One workgroup (4 wavefronts) handles one (unit, split): a contiguous range of the
+// unit's tiles, a tile being 8 consecutive 1 KiB wave-loads of one selected block.  In a wave-load
+// every lane reads 16 bytes; LPR = row_bytes / 16 adjacent lanes cover one token row, so a
+// wavefront reads RPW = 64 / LPR whole rows (1 KiB, fully coalesced) per instruction.  A lane keeps
+// the slice of q it needs in registers (all G heads of the group), forms partial dot products,
+// and the LPR lanes of a row add them up with DPP row operations (no LDS).  The row's scores then
+// sit in exactly the lanes that hold the matching slice of the V row, so the P.V update needs no
+// data movement either.  Each row-group of lanes carries its own online-softmax state
+// (m, l, acc[G][slice]); states are merged once at the end: across row-groups by lane exchange,
+// across waves through LDS, across splits by the combine kernel.
+//
+// Logits are kept in the log2 domain: z' = (scale*log2 e) q.k + b*log2 e, p = 2^(z' - m').
+#include <cmath>
+
+#include "nosa_internal.h"
+
+namespace nosa {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kSteps = 8;  // wave-loads per tile
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+struct DecodeArgs {
+  const void* q;
+  const void* pool_k;
+  const void* pool_v;
+  const float* pool_bias;
+  const int32_t* sel_idx;
+  const int32_t* n_sel;
+  const int32_t* slot_of_block;
+  const int32_t* n_tokens;
+  float* part_o;   // [units][splits][G][D] un-normalised
+  float* part_ml;  // [units][splits][G][2]  (m in log2 domain, l)
+  void* out;
+  float* lse;
+  int n_kv_heads, gpu_slots, k_blocks, max_blocks, splits;
+  float scale_log2e;
+};
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true);
+  return x + __int_as_float(y);
+}
+
+// Sum over the LPR adjacent lanes that hold one row; every one of them receives the total.
+template <int LPR>
+__device__ __forceinline__ float row_sum(float x) {
+  x = dpp_add<0xB1>(x);                          // quad_perm [1,0,3,2]  : lane ^ 1
+  x = dpp_add<0x4E>(x);                          // quad_perm [2,3,0,1]  : lane ^ 2
+  x = dpp_add<0x141>(x);                         // row_half_mirror      : the other quad of 8
+  if constexpr (LPR >= 16) x = dpp_add<0x140>(x);  // row_mirror           : the other half of 16
+  if constexpr (LPR >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int DT>
+struct Vec;  // 16 bytes of one row as seen by one lane
+
+template <>
+struct Vec<NOSA_DTYPE_BF16> {
+  static constexpr int kElems = 8;
+  static constexpr int kBytes = 2;
+  uint4 raw;
+  __device__ __forceinline__ float dot(const Vec& o) const {
+    float d = 0.f;
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, raw.x), __builtin_bit_cast(bf16x2_t, o.raw.x), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, raw.y), __builtin_bit_cast(bf16x2_t, o.raw.y), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, raw.z), __builtin_bit_cast(bf16x2_t, o.raw.z), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, raw.w), __builtin_bit_cast(bf16x2_t, o.raw.w), d, false);
+    return d;
+  }
+  __device__ __forceinline__ void widen(float (&f)[8]) const {
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+
+template <>
+struct Vec<NOSA_DTYPE_F32> {
+  static constexpr int kElems = 4;
+  static constexpr int kBytes = 4;
+  uint4 raw;
+  __device__ __forceinline__ float dot(const Vec& o) const {
+    float d = __uint_as_float(raw.x) * __uint_as_float(o.raw.x);
+    d = fmaf(__uint_as_float(raw.y), __uint_as_float(o.raw.y), d);
+    d = fmaf(__uint_as_float(raw.z), __uint_as_float(o.raw.z), d);
+    d = fmaf(__uint_as_float(raw.w), __uint_as_float(o.raw.w), d);
+    return d;
+  }
+  __device__ __forceinline__ void widen(float (&f)[4]) const {
+    f[0] = __uint_as_float(raw.x);
+    f[1] = __uint_as_float(raw.y);
+    f[2] = __uint_as_float(raw.z);
+    f[3] = __uint_as_float(raw.w);
+  }
+};
+
+__device__ __forceinline__ void store_out(void* out, size_t idx, float v, int dt) {
+  if (dt == NOSA_DTYPE_F32) {
+    ((float*)out)[idx] = v;
+  } else {
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) {
+      u = (u >> 16) | 0x40;
+    } else {
+      u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest even
+      u >>= 16;
+    }
+    ((uint16_t*)out)[idx] = (uint16_t)u;
+  }
+}
+
+template <int DT, int D, int G, bool HAS_BIAS>
+__global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeArgs a) {
+  using V = Vec<DT>;
+  constexpr int EPL = V::kElems;             // elements per lane per load
+  constexpr int LPR = D / EPL;               // lanes per row
+  constexpr int RPW = kWave / LPR;           // rows per wave-load
+  constexpr int TILE = RPW * kSteps;         // tokens per tile
+  constexpr int TPB = kBlockTokens / TILE;   // tiles per block
+  static_assert(TPB >= 1 && TPB * TILE == kBlockTokens, "tile must divide the block");
+  constexpr float NEG_INF = -INFINITY;
+
+  __shared__ int s_slot[kMaxSelBlocks];
+  __shared__ int s_valid[kMaxSelBlocks];
+  __shared__ float s_m[kWaves][G];
+  __shared__ float s_l[kWaves][G];
+  __shared__ float s_acc[kWaves][G][D];
+
+  const int unit = blockIdx.y;
+  const int split = blockIdx.x;
+  const int b = unit / a.n_kv_heads;
+  const int h = unit % a.n_kv_heads;
+  const int tid = threadIdx.x;
+  const int lane = tid % kWave;
+  const int wave = tid / kWave;
+  const int r = lane / LPR;   // row-group within the wave
+  const int c = lane % LPR;   // 16-byte slice of the row
+
+  const int n_sel = min(a.n_sel[unit], a.k_blocks);
+  const int T = a.n_tokens[b];
+  for (int i = tid; i < n_sel; i += kThreads) {
+    const int J = a.sel_idx[(size_t)unit * a.k_blocks + i];
+    int slot = -1, valid = 0;
+    if (J >= 0 && J < a.max_blocks) {
+      slot = a.slot_of_block[(size_t)unit * a.max_blocks + J];
+      valid = min(kBlockTokens, T - J * kBlockTokens);
+    }
+    if (slot < 0 || slot >= a.gpu_slots) valid = 0;   // never dereference a bad slot
+    s_slot[i] = slot;
+    s_valid[i] = valid;
+  }
+
+  // q slice of this lane for all heads of the group
+  V qv[G];
+  {
+    const uint4* qp = (const uint4*)((const char*)a.q + ((size_t)b * a.n_kv_heads * G + (size_t)h * G) * D * V::kBytes);
+#pragma unroll
+    for (int g = 0; g < G; ++g) qv[g].raw = qp[g * LPR + c];
+  }
+
+  float m[G], l[G], acc[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = NEG_INF;
+    l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+  }
+  __syncthreads();
+
+  const int total_tiles = n_sel * TPB;
+  const int t_begin = (int)(((long long)split * total_tiles) / a.splits);
+  const int t_end = (int)(((long long)(split + 1) * total_tiles) / a.splits);
+  constexpr size_t kBlockBytes = (size_t)kBlockTokens * D * V::kBytes;
+  constexpr int kStepStride = kWave;  // in uint4 units: one wave-load is 1 KiB
+
+  for (int t = t_begin + wave; t < t_end; t += kWaves) {
+    const int i_blk = t / TPB;
+    const int part = t % TPB;
+    const int nvalid = s_valid[i_blk] - part * TILE;
+    if (nvalid <= 0) continue;
+    const size_t slot_lin = (size_t)unit * a.gpu_slots + s_slot[i_blk];
+    const size_t row0 = (size_t)part * TILE + r;
+    const uint4* kp = (const uint4*)((const char*)a.pool_k + slot_lin * kBlockBytes) + row0 * LPR + c;
+    const uint4* vp = (const uint4*)((const char*)a.pool_v + slot_lin * kBlockBytes) + row0 * LPR + c;
+
+    V kx[kSteps], vx[kSteps];
+    float bx[kSteps];
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) kx[i].raw = kp[i * kStepStride];
+    if constexpr (HAS_BIAS) {
+      const float* bp = a.pool_bias + slot_lin * kBlockTokens + row0;
+#pragma unroll
+      for (int i = 0; i < kSteps; ++i) bx[i] = bp[i * RPW];
+    }
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) vx[i].raw = vp[i * kStepStride];
+
+    float s[G][kSteps];
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) {
+      float bl = 0.f;
+      if constexpr (HAS_BIAS) bl = bx[i] * 1.4426950408889634f;
+#pragma unroll
+      for (int g = 0; g < G; ++g) s[g][i] = fmaf(row_sum<LPR>(kx[i].dot(qv[g])), a.scale_log2e, bl);
+    }
+
+    const bool masked = nvalid < TILE;   // wave-uniform: only the partial tail block takes this path
+    if (masked) {
+#pragma unroll
+      for (int i = 0; i < kSteps; ++i) {
+        const bool ok = (i * RPW + r) < nvalid;
+#pragma unroll
+        for (int g = 0; g < G; ++g) s[g][i] = ok ? s[g][i] : NEG_INF;
+        if (!ok) vx[i].raw = make_uint4(0, 0, 0, 0);   // stale bytes beyond T must not reach the sum
+      }
+    }
+
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float mt = s[g][0];
+#pragma unroll
+      for (int i = 1; i < kSteps; ++i) mt = fmaxf(mt, s[g][i]);
+      const float m_new = fmaxf(m[g], mt);
+      const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
+      const float alpha = fast_exp2(m[g] - m_use);
+      m[g] = m_new;
+      l[g] *= alpha;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
+#pragma unroll
+      for (int i = 0; i < kSteps; ++i) s[g][i] = fast_exp2(s[g][i] - m_use);
+    }
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) {
+      float vf[EPL];
+      vx[i].widen(vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float p = s[g][i];
+        l[g] += p;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
+      }
+    }
+  }
+
+  // ---- merge the RPW row-group states of this wave (lane exchange) ----
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float M = m[g];
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
+    const float sc = (m[g] == NEG_INF) ? 0.f : fast_exp2(m[g] - M);
+    float lg = l[g] * sc;
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) lg += __shfl_xor(lg, off);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      float x = acc[g][e] * sc;
+#pragma unroll
+      for (int off = LPR; off < kWave; off <<= 1) x += __shfl_xor(x, off);
+      acc[g][e] = x;
+    }
+    m[g] = M;
+    l[g] = lg;
+  }
+  if (r == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) s_acc[wave][g][c * EPL + e] = acc[g][e];
+      if (c == 0) {
+        s_m[wave][g] = m[g];
+        s_l[wave][g] = l[g];
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- merge the waves; write the partial result (or the output when there is one split) ----
+  for (int idx = tid; idx < G * D; idx += kThreads) {
+    const int g = idx / D, e = idx % D;
+    float M = s_m[0][g];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w][g]);
+    float L = 0.f, O = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float sc = (s_m[w][g] == NEG_INF) ? 0.f : fast_exp2(s_m[w][g] - M);
+      L = fmaf(s_l[w][g], sc, L);
+      O = fmaf(s_acc[w][g][e], sc, O);
+    }
+    if (a.splits == 1) {
+      const size_t o = ((size_t)b * a.n_kv_heads * G + (size_t)h * G + g) * D + e;
+      store_out(a.out, o, L > 0.f ? O / L : 0.f, DT);
+      if (a.lse && e == 0) a.lse[(size_t)b * a.n_kv_heads * G + h * G + g] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : NEG_INF;
+    } else {
+      const size_t pidx = ((size_t)unit * a.splits + split) * G + g;
+      a.part_o[pidx * D + e] = O;
+      if (e == 0) {
+        a.part_ml[pidx * 2] = M;
+        a.part_ml[pidx * 2 + 1] = L;
+      }
+    }
+  }
+}
+
+// One workgroup per unit: merges the split partial results with log-sum-exp weights.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void decode_combine_kernel(const float* __restrict__ part_o,
+                                                                  const float* __restrict__ part_ml, void* out,
+                                                                  float* lse, int n_kv_heads, int G, int D, int splits) {
+  const int unit = blockIdx.x;
+  const int b = unit / n_kv_heads, h = unit % n_kv_heads;
+  for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+    const int g = idx / D, e = idx % D;
+    const size_t p0 = ((size_t)unit * splits) * G + g;
+    float M = -INFINITY;
+    for (int s = 0; s < splits; ++s) M = fmaxf(M, part_ml[(p0 + (size_t)s * G) * 2]);
+    float L = 0.f, O = 0.f;
+    for (int s = 0; s < splits; ++s) {
+      const size_t pi = p0 + (size_t)s * G;
+      const float ms = part_ml[pi * 2];
+      const float sc = (ms == -INFINITY) ? 0.f : fast_exp2(ms - M);
+      L = fmaf(part_ml[pi * 2 + 1], sc, L);
+      O = fmaf(part_o[pi * D + e], sc, O);
+    }
+    const size_t o = ((size_t)b * n_kv_heads * G + (size_t)h * G + g) * D + e;
+    store_out(out, o, L > 0.f ? O / L : 0.f, DT);
+    if (lse && e == 0) lse[(size_t)b * n_kv_heads * G + h * G + g] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
+  }
+}
+
+template <int DT, int D, int G>
+void launch_partial(const DecodeArgs& a, dim3 grid, hipStream_t s) {
+  if (a.pool_bias)
+    hipLaunchKernelGGL((decode_partial_kernel<DT, D, G, true>), grid, dim3(kThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL((decode_partial_kernel<DT, D, G, false>), grid, dim3(kThreads), 0, s, a);
+}
+
+template <int DT, int D>
+bool dispatch_group(int g, const DecodeArgs& a, dim3 grid, hipStream_t s) {
+  switch (g) {
+    case 1: launch_partial<DT, D, 1>(a, grid, s); return true;
+    case 2: launch_partial<DT, D, 2>(a, grid, s); return true;
+    case 3: launch_partial<DT, D, 3>(a, grid, s); return true;
+    case 4: launch_partial<DT, D, 4>(a, grid, s); return true;
+    case 6: launch_partial<DT, D, 6>(a, grid, s); return true;
+    case 8: launch_partial<DT, D, 8>(a, grid, s); return true;
+    case 12: launch_partial<DT, D, 12>(a, grid, s); return true;
+    case 16: launch_partial<DT, D, 16>(a, grid, s); return true;
+    default: return false;
+  }
+}
+
+}  // namespace
+
+bool decode_supports_group(int g) {
+  return g == 1 || g == 2 || g == 3 || g == 4 || g == 6 || g == 8 || g == 12 || g == 16;
+}
+
+int decode_default_splits(const nosa_params& p) {
+  const int units = p.batch * p.n_kv_heads;
+  const int row_bytes = p.head_dim * (p.dtype == NOSA_DTYPE_F32 ? 4 : 2);
+  const int tile_tokens = (kWave * 16 / row_bytes) * kSteps;
+  const int tiles = p.k_blocks * (kBlockTokens / tile_tokens);
+  int s = (2048 + units - 1) / units;           // enough workgroups to cover 256 CUs several times
+  const int cap = tiles / kWaves > 1 ? tiles / kWaves : 1;   // at least one tile per wave
+  if (s > cap) s = cap;
+  if (s > NOSA_MAX_SPLITS) s = NOSA_MAX_SPLITS;
+  if (s < 1) s = 1;
+  return s;
+}
+
+int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v, const float* pool_bias,
+                  const int32_t* sel_idx, const int32_t* n_sel, const int32_t* slot_of_block,
+                  const int32_t* n_tokens, void* out, float* lse) {
+  const nosa_params& p = ctx->p;
+  const int G = ctx->group, D = p.head_dim, S = ctx->splits;
+  DecodeArgs a;
+  a.q = q; a.pool_k = pool_k; a.pool_v = pool_v; a.pool_bias = pool_bias;
+  a.sel_idx = sel_idx; a.n_sel = n_sel; a.slot_of_block = slot_of_block; a.n_tokens = n_tokens;
+  a.part_o = (float*)ctx->ws;
+  a.part_ml = a.part_o ? a.part_o + (size_t)ctx->units * S * G * D : nullptr;
+  a.out = out; a.lse = lse;
+  a.n_kv_heads = p.n_kv_heads; a.gpu_slots = p.gpu_slots; a.k_blocks = p.k_blocks; a.max_blocks = p.max_blocks;
+  a.splits = S;
+  a.scale_log2e = ctx->scale * 1.4426950408889634f;
+  const dim3 grid(S, ctx->units);
+  bool ok;
+  {
+    TimedLaunch tl(ctx, NOSA_KERNEL_DECODE, ctx->main);
+    if (p.dtype == NOSA_DTYPE_BF16)
+      ok = D == 128 ? dispatch_group<NOSA_DTYPE_BF16, 128>(G, a, grid, ctx->main) : dispatch_group<NOSA_DTYPE_BF16, 64>(G, a, grid, ctx->main);
+    else
+      ok = D == 128 ? dispatch_group<NOSA_DTYPE_F32, 128>(G, a, grid, ctx->main) : dispatch_group<NOSA_DTYPE_F32, 64>(G, a, grid, ctx->main);
+  }
+  NOSA_REQUIRE(ctx, ok, NOSA_ESHAPE, "GQA group %d unsupported", G);
+  NOSA_HIP(ctx, hipGetLastError());
+  if (S > 1) {
+    TimedLaunch tl(ctx, NOSA_KERNEL_COMBINE, ctx->main);
+    if (p.dtype == NOSA_DTYPE_BF16)
+      hipLaunchKernelGGL((decode_combine_kernel<NOSA_DTYPE_BF16>), dim3(ctx->units), dim3(kThreads), 0, ctx->main,
+                         a.part_o, a.part_ml, out, lse, p.n_kv_heads, G, D, S);
+    else
+      hipLaunchKernelGGL((decode_combine_kernel<NOSA_DTYPE_F32>), dim3(ctx->units), dim3(kThreads), 0, ctx->main,
+                         a.part_o, a.part_ml, out, lse, p.n_kv_heads, G, D, S);
+    NOSA_HIP(ctx, hipGetLastError());
+  }
+  return NOSA_OK;
+}
+
+}  // namespace nosa

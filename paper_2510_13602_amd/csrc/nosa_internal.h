@@ -1,0 +1,94 @@
+// Internal declarations shared by the translation units of libnosa (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/nosa.h"
+
+namespace nosa {
+
+constexpr int kWave = 64;            // CDNA wavefront
+constexpr int kBlockTokens = 64;     // n_b supported by this build
+constexpr int kMaxTimed = 4096;      // launches kept per kernel between timing reads
+constexpr int kMaxSelBlocks = 256;   // K limit of the decode kernel's slot table
+constexpr int kMaxSelectBlocks = 4096;  // max_blocks limit of the selection kernel (LDS-resident keys)
+
+struct Timing {
+  hipEvent_t* start = nullptr;
+  hipEvent_t* stop = nullptr;
+  int n = 0;
+};
+
+}  // namespace nosa
+
+struct nosa_ctx {
+  nosa_params p;
+  int group = 1;            // G = Hq / Hkv
+  int units = 0;            // B * Hkv
+  float scale = 0.f;        // softmax scale actually used
+  int device = 0;
+  hipStream_t main = nullptr;
+  hipStream_t side = nullptr;
+  hipEvent_t ev_select = nullptr;   // recorded on main after the selection kernel
+  hipEvent_t ev_fetch = nullptr;    // recorded on side after the gather kernel
+  bool select_recorded = false;
+  bool fetch_pending = false;
+  int overlap = 1;
+  int splits = 1;
+  void* ws = nullptr;
+  size_t ws_bytes = 0;
+  bool timing = false;
+  nosa::Timing timed[NOSA_KERNEL_COUNT];
+  char err[512] = {0};
+};
+
+namespace nosa {
+
+int set_error(nosa_ctx* ctx, int code, const char* fmt, ...);
+
+// Brackets one kernel launch with events when timing is on.
+struct TimedLaunch {
+  nosa_ctx* ctx;
+  int kernel;
+  hipStream_t stream;
+  int slot = -1;
+  TimedLaunch(nosa_ctx* c, int k, hipStream_t s);
+  ~TimedLaunch();
+};
+
+#define NOSA_HIP(ctx, call)                                                                   \
+  do {                                                                                        \
+    hipError_t e__ = (call);                                                                  \
+    if (e__ != hipSuccess)                                                                    \
+      return nosa::set_error((ctx), NOSA_EHIP, "%s failed: %s (%s:%d)", #call,                \
+                             hipGetErrorString(e__), __FILE__, __LINE__);                     \
+  } while (0)
+
+#define NOSA_REQUIRE(ctx, cond, code, ...)                                                    \
+  do {                                                                                        \
+    if (!(cond)) return nosa::set_error((ctx), (code), __VA_ARGS__);                          \
+  } while (0)
+
+// kernel launchers (one per translation unit); all validate nothing: callers have done so
+int launch_block_score(nosa_ctx* ctx, const void* q, const void* k_pooled, const float* se_pooled,
+                       const int32_t* n_tokens, float* sq_blk, float* se_blk);
+int launch_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const int32_t* n_tokens,
+                  int32_t* sel_idx, int32_t* n_sel, int32_t* slot_of_block, int32_t* block_of_slot,
+                  int32_t* load_list, int32_t* n_load);
+int launch_fetch(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const void* host_v,
+                 const float* host_bias, void* pool_k, void* pool_v, float* pool_bias,
+                 const int32_t* load_list, const int32_t* n_load);
+int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v,
+                  const float* pool_bias, const int32_t* sel_idx, const int32_t* n_sel,
+                  const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse);
+int launch_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const int32_t* n_tokens,
+                       void* k_pooled, float* se_pooled);
+bool decode_supports_group(int g);
+int decode_default_splits(const nosa_params& p);
+
+}  // namespace nosa

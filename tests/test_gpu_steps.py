@@ -1,0 +1,76 @@
+"""Whole decode steps (score -> select -> fetch -> attention) through the C ABI against the
+oracle, over several steps with the residency state carried along (needs an MI355X).
+
+Covers the Tiny and the 1B-shaped configuration in full, reduced-batch versions of the 3B- and
+8B-shaped ones, the serial (no side stream) order, and poisoned victim slots.
+"""
+import numpy as np
+import pytest
+import torch
+
+from nosa_inputs import CONFIGS, random_residency
+from pipeline import run_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def test_tiny_all_steps():
+    w = CONFIGS["tiny"]
+    rec = run_parity(w, seed=0, steps=w.steps)
+    assert rec[0]["n_load_max"] == w.k_blocks                       # cold start fills the pool
+    assert max(r["n_load_max"] for r in rec[1:]) <= 2                # <= 2 newly fetched blocks per step
+    print("tiny: max err", max(r["err"] for r in rec), "retries", sum(r["retries"] for r in rec), flush=True)
+
+
+def test_tiny_ragged_context_serial_order():
+    w = CONFIGS["tiny"].replace(context=2048 - 37)
+    run_parity(w, seed=1, steps=6, overlap=False)
+
+
+def test_1b_shaped_half_resident():
+    """batch 16, 16 q heads / 2 KV heads, d64, 8192 tokens, C = 64 of 128 blocks resident at start."""
+    w = CONFIGS["1b"]
+    res = random_residency(w, seed=0, layer=0, n_blocks=w.context // w.block_size)
+    rec = run_parity(w, seed=0, steps=12, residency=res)
+    print("1b: n_load mean per step", [round(r["n_load_mean"], 2) for r in rec], flush=True)
+
+
+def test_1b_overlap_and_serial_give_identical_bits():
+    w = CONFIGS["1b"].replace(batch=4)
+    outs = []
+    for overlap in (True, False):
+        import paper_2510_13602_amd as nosa
+        from helpers import gpu_params, to_np
+        from nosa_inputs import QueryStream, make_layer
+        from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+        layer = make_layer(w, 5, 0)
+        ctx = nosa.Nosa(gpu_params(w))
+        ctx.set_overlap(overlap)
+        gl = LayerCache(ctx, pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"]),
+                        torch.full((w.batch,), w.context, dtype=torch.int32))
+        gl.rebuild_pooled()
+        gl.pool_k.fill_(float("nan")); gl.pool_v.fill_(float("nan")); gl.pool_bias.fill_(float("nan"))
+        qs = QueryStream(w, 5, 0)
+        res = []
+        for t in range(8):
+            o = gl.step(qs.next(t).to("cuda:0"))
+            res.append((to_np(o).copy(), gl.sel_idx.cpu().numpy().copy(), gl.n_load.cpu().numpy().copy()))
+        torch.cuda.synchronize()
+        outs.append(res)
+        ctx.close()
+    for (o1, s1, n1), (o2, s2, n2) in zip(*outs):
+        assert o1.tobytes() == o2.tobytes() and (s1 == s2).all() and (n1 == n2).all()
+
+
+def test_3b_shaped_reduced_batch():
+    """24 q heads / 4 KV heads (group 6), d128, 16384 tokens, K = 64, AR(1) queries; batch cut to 2."""
+    w = CONFIGS["3b"].replace(batch=2)
+    rec = run_parity(w, seed=0, steps=6)
+    print("3b: n_load mean per step", [round(r["n_load_mean"], 2) for r in rec], flush=True)
+
+
+def test_8b_shaped_reduced_batch():
+    """32 q heads / 8 KV heads (group 4), d128, 32768 tokens, K = 64, heavy hitters; batch cut to 1."""
+    w = CONFIGS["8b"].replace(batch=1)
+    rec = run_parity(w, seed=0, steps=5)
+    print("8b: n_load mean per step", [round(r["n_load_mean"], 2) for r in rec], flush=True)
