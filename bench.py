@@ -33,8 +33,12 @@ def parse_args():
     ap.add_argument("--no-overlap", action="store_true", help="run the fetch on the main stream")
     ap.add_argument("--resident", action="store_true", help="kernel-only mode: same queries every step, so nothing is fetched")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-batch", type=int, default=4)
+    ap.add_argument("--cpu-sample-batch", type=int, default=16)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work the oracle baseline is given")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run five plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
     return ap.parse_args()
 
 
@@ -54,16 +58,15 @@ def step_bytes_per_unit(w) -> int:
     return decode_bytes_per_unit(w) + w.n_sub_max * (w.head_dim * e + 4)
 
 
-def cpu_baseline(w, seed, sample_batch, steps=2):
-    """The fp64 oracle, as it stands, timed on this machine's host cores on a slice of the same workload."""
+def cpu_baseline(w, host, queries, sample_batch, seconds):
+    """The fp64 oracle, as it stands, timed on this machine's host cores on a slice (the first
+    ``sample_batch`` batch elements) of the very tensors the GPU run used."""
     import numpy as np
     import oracle
-    from nosa_inputs import QueryStream, make_layer
-    oracle_params, to_np = oracle.params_from_workload, oracle.to_np
+    to_np = oracle.to_np
     ws = w.replace(batch=sample_batch)
-    layer = make_layer(ws, seed, 0)
-    p = oracle_params(ws)
-    hk, hv, hb = to_np(layer["host_k"]), to_np(layer["host_v"]), to_np(layer["host_bias"])
+    p = oracle.params_from_workload(ws)
+    hk, hv, hb = (to_np(t[:sample_batch]) for t in host)
     n_tok = np.full((ws.batch,), ws.context, np.int32)
     kc, sec = oracle.pool(p, hk, hb, n_tok)
     B, H, C, nb, d = ws.batch, ws.n_kv_heads, ws.gpu_slots, ws.block_size, ws.head_dim
@@ -71,10 +74,10 @@ def cpu_baseline(w, seed, sample_batch, steps=2):
     pb = np.zeros((B, H, C, nb), np.float32)
     sob = np.full((B, H, ws.max_blocks), -1, np.int32)
     bos = np.full((B, H, C), -1, np.int32)
-    qs = QueryStream(ws, seed, 0)
+    qs = [to_np(q[:sample_batch]) for q in queries]
 
     def one(t):
-        q = to_np(qs.next(t))
+        q = qs[t % len(qs)]
         sq, se = oracle.block_score(p, q, kc, sec, n_tok)
         sel, n_sel = oracle.select(p, sq, se, n_tok)
         ll, n_load = oracle.load(p, sel, n_sel, sob, bos)
@@ -82,13 +85,14 @@ def cpu_baseline(w, seed, sample_batch, steps=2):
         oracle.attention(p, q, pk, pv, pb, sel, n_sel, sob, n_tok)
 
     one(0)                                   # cold start (fills the pool), untimed
-    t0 = time.perf_counter()
-    for t in range(1, 1 + steps):
-        one(t)
+    steps, t0 = 0, time.perf_counter()
+    while steps < 2 or time.perf_counter() - t0 < seconds:
+        steps += 1
+        one(steps)
     dt = time.perf_counter() - t0
-    units = ws.units * steps
-    return {"value": units / dt, "unit": "unit-steps/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{steps} steps of {ws.units} units (batch {sample_batch} of {w.batch}) of the {w.name} workload, "
+    return {"value": ws.units * steps / dt, "unit": "unit-steps/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{steps} whole steps (score, select, load, fetch, attention) of {ws.units} units = batch "
+                      f"{sample_batch} of {w.batch} of the {w.name}-shaped workload, same tensors as the GPU run, "
                       f"fp64, OpenMP over units, {dt:.1f} s"}
 
 
@@ -107,6 +111,14 @@ def main():
         print("bench.py: no GPU; the NOSA hot path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
     dev = "cuda:0"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "copies": 5}))
+        return
     w = CONFIGS[args.workload]
     L = args.layers or min(w.layers, 32)
     LH = max(1, min(args.host_layers, L))
@@ -158,7 +170,7 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
 
-    ctx.timing_enable(True)
+    ctx.timing_enable(not args.no_kernel_timing)
     for k in range(5):
         ctx.timing_read(k)
     torch.cuda.synchronize()
@@ -214,9 +226,9 @@ def main():
         "setup_s": setup_s,
     }
     if not args.no_cpu_baseline:
-        for lc in layers:
-            del lc
-        line["cpu_baseline"] = cpu_baseline(w, args.seed, min(args.cpu_sample_batch, w.batch))
+        layers.clear()
+        torch.cuda.empty_cache()
+        line["cpu_baseline"] = cpu_baseline(w, hosts[0], queries[0], min(args.cpu_sample_batch, w.batch), args.cpu_seconds)
     ctx.close()
     print(json.dumps(line), flush=True)
 

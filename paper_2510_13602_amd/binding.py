@@ -13,7 +13,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libnosa.so")
+LIB_PATH = os.environ.get("NOSA_LIBRARY", os.path.join(_HERE, "libnosa.so"))   # override: experiments only
 
 NOSA_OK, NOSA_EINVAL, NOSA_ESHAPE, NOSA_EHIP = 0, -1, -2, -3
 DTYPE_F32, DTYPE_BF16 = 0, 1

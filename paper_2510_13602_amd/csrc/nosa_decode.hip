@@ -6,15 +6,16 @@
 // organised around wide coalesced loads, not around matrix cores.
 //
 // Mapping.  One workgroup (4 wavefronts) handles one (unit, split): a contiguous range of the
-// unit's tiles, a tile being 8 consecutive 1 KiB wave-loads of one selected block.  In a wave-load
-// every lane reads 16 bytes; LPR = row_bytes / 16 adjacent lanes cover one token row, so a
-// wavefront reads RPW = 64 / LPR whole rows (1 KiB, fully coalesced) per instruction.  A lane keeps
-// the slice of q it needs in registers (all G heads of the group), forms partial dot products,
-// and the LPR lanes of a row add them up with DPP row operations (no LDS).  The row's scores then
-// sit in exactly the lanes that hold the matching slice of the V row, so the P.V update needs no
-// data movement either.  Each row-group of lanes carries its own online-softmax state
-// (m, l, acc[G][slice]); states are merged once at the end: across row-groups by lane exchange,
-// across waves through LDS, across splits by the combine kernel.
+// unit's tiles, a tile being 8 wave-loads (8 KiB) of K and as many of V from one selected block.
+// In a wave-load every lane reads 16 bytes; 8 adjacent lanes cover one 128-byte line of a token
+// row, so one instruction reads whole lines of 8 rows, and VPL = row_bytes / 128 instructions
+// read the 8 rows completely ("a step").  A lane keeps the slices of q it needs in registers (all
+// G heads of the group), forms partial dot products, and the 8 lanes of a row add them up with
+// three DPP row operations (no LDS).  The row's scores then sit in exactly the lanes that hold the
+// matching slices of the V row, so the P.V update needs no data movement either.  Each of the 8
+// row-groups of lanes carries its own online-softmax state (m, l, acc[G][slices]); states are
+// merged once at the end: across row-groups by lane exchange, across waves through LDS, across
+// splits by the combine kernel.
 //
 // Logits are kept in the log2 domain: z' = (scale*log2 e) q.k + b*log2 e, p = 2^(z' - m').
 #include <cmath>
@@ -27,9 +28,21 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kSteps = 8;  // wave-loads per tile
+#ifndef NOSA_DECODE_LOADS
+#define NOSA_DECODE_LOADS 8
+#endif
+constexpr int kLoads = NOSA_DECODE_LOADS;   // 16-byte loads of K (and of V) per lane and tile
+constexpr int kLPR = 8;     // lanes per row: 8 x 16 B = one 128-byte line
+constexpr int kRPW = kWave / kLPR;   // rows per step
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// K/V rows are read exactly once per step: stream them past the caches (non-temporal).
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 struct DecodeArgs {
   const void* q;
@@ -54,14 +67,11 @@ __device__ __forceinline__ float dpp_add(float x) {
   return x + __int_as_float(y);
 }
 
-// Sum over the LPR adjacent lanes that hold one row; every one of them receives the total.
-template <int LPR>
+// Sum over the 8 adjacent lanes that hold one row; every one of them receives the total.
 __device__ __forceinline__ float row_sum(float x) {
-  x = dpp_add<0xB1>(x);                          // quad_perm [1,0,3,2]  : lane ^ 1
-  x = dpp_add<0x4E>(x);                          // quad_perm [2,3,0,1]  : lane ^ 2
-  x = dpp_add<0x141>(x);                         // row_half_mirror      : the other quad of 8
-  if constexpr (LPR >= 16) x = dpp_add<0x140>(x);  // row_mirror           : the other half of 16
-  if constexpr (LPR >= 32) x += __shfl_xor(x, 16);
+  x = dpp_add<0xB1>(x);    // quad_perm [1,0,3,2]  : lane ^ 1
+  x = dpp_add<0x4E>(x);    // quad_perm [2,3,0,1]  : lane ^ 2
+  x = dpp_add<0x141>(x);   // row_half_mirror      : the other quad of the 8
   return x;
 }
 
@@ -131,12 +141,14 @@ __device__ __forceinline__ void store_out(void* out, size_t idx, float v, int dt
 template <int DT, int D, int G, bool HAS_BIAS>
 __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeArgs a) {
   using V = Vec<DT>;
-  constexpr int EPL = V::kElems;             // elements per lane per load
-  constexpr int LPR = D / EPL;               // lanes per row
-  constexpr int RPW = kWave / LPR;           // rows per wave-load
-  constexpr int TILE = RPW * kSteps;         // tokens per tile
-  constexpr int TPB = kBlockTokens / TILE;   // tiles per block
-  static_assert(TPB >= 1 && TPB * TILE == kBlockTokens, "tile must divide the block");
+  constexpr int EPL = V::kElems;                 // elements per 16-byte load
+  constexpr int RP = D / EPL;                    // row pitch in 16-byte vectors
+  constexpr int VPL = RP / kLPR;                 // loads per lane and row (row_bytes / 128)
+  constexpr int STEPS = kLoads / VPL;            // steps (of 8 rows) per tile
+  constexpr int TILE = kRPW * STEPS;             // tokens per tile
+  constexpr int TPB = kBlockTokens / TILE;       // tiles per block
+  constexpr int LE = VPL * EPL;                  // elements of a row held by one lane
+  static_assert(VPL >= 1 && STEPS >= 1 && TPB >= 1 && TPB * TILE == kBlockTokens, "tile must divide the block");
   constexpr float NEG_INF = -INFINITY;
 
   __shared__ int s_slot[kMaxSelBlocks];
@@ -152,8 +164,8 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
   const int tid = threadIdx.x;
   const int lane = tid % kWave;
   const int wave = tid / kWave;
-  const int r = lane / LPR;   // row-group within the wave
-  const int c = lane % LPR;   // 16-byte slice of the row
+  const int r = lane / kLPR;   // row-group within the wave
+  const int c = lane % kLPR;   // 16-byte slice of a 128-byte line
 
   const int n_sel = min(a.n_sel[unit], a.k_blocks);
   const int T = a.n_tokens[b];
@@ -169,21 +181,23 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
     s_valid[i] = valid;
   }
 
-  // q slice of this lane for all heads of the group
-  V qv[G];
+  // q slices of this lane for all heads of the group: line v of the row, 16-byte slice c
+  V qv[G][VPL];
   {
     const uint4* qp = (const uint4*)((const char*)a.q + ((size_t)b * a.n_kv_heads * G + (size_t)h * G) * D * V::kBytes);
 #pragma unroll
-    for (int g = 0; g < G; ++g) qv[g].raw = qp[g * LPR + c];
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) qv[g][v].raw = qp[g * RP + v * kLPR + c];
   }
 
-  float m[G], l[G], acc[G][EPL];
+  float m[G], l[G], acc[G][LE];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     m[g] = NEG_INF;
     l[g] = 0.f;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+    for (int e = 0; e < LE; ++e) acc[g][e] = 0.f;
   }
   __syncthreads();
 
@@ -191,7 +205,6 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
   const int t_begin = (int)(((long long)split * total_tiles) / a.splits);
   const int t_end = (int)(((long long)(split + 1) * total_tiles) / a.splits);
   constexpr size_t kBlockBytes = (size_t)kBlockTokens * D * V::kBytes;
-  constexpr int kStepStride = kWave;  // in uint4 units: one wave-load is 1 KiB
 
   for (int t = t_begin + wave; t < t_end; t += kWaves) {
     const int i_blk = t / TPB;
@@ -200,38 +213,50 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
     if (nvalid <= 0) continue;
     const size_t slot_lin = (size_t)unit * a.gpu_slots + s_slot[i_blk];
     const size_t row0 = (size_t)part * TILE + r;
-    const uint4* kp = (const uint4*)((const char*)a.pool_k + slot_lin * kBlockBytes) + row0 * LPR + c;
-    const uint4* vp = (const uint4*)((const char*)a.pool_v + slot_lin * kBlockBytes) + row0 * LPR + c;
+    const uint4* kp = (const uint4*)((const char*)a.pool_k + slot_lin * kBlockBytes) + row0 * RP + c;
+    const uint4* vp = (const uint4*)((const char*)a.pool_v + slot_lin * kBlockBytes) + row0 * RP + c;
 
-    V kx[kSteps], vx[kSteps];
-    float bx[kSteps];
+    V kx[STEPS][VPL], vx[STEPS][VPL];
+    float bx[STEPS];
 #pragma unroll
-    for (int i = 0; i < kSteps; ++i) kx[i].raw = kp[i * kStepStride];
+    for (int i = 0; i < STEPS; ++i)
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) kx[i][v].raw = load_stream(kp + i * (kRPW * RP) + v * kLPR);
     if constexpr (HAS_BIAS) {
       const float* bp = a.pool_bias + slot_lin * kBlockTokens + row0;
 #pragma unroll
-      for (int i = 0; i < kSteps; ++i) bx[i] = bp[i * RPW];
+      for (int i = 0; i < STEPS; ++i) bx[i] = __builtin_nontemporal_load(bp + i * kRPW);
     }
 #pragma unroll
-    for (int i = 0; i < kSteps; ++i) vx[i].raw = vp[i * kStepStride];
-
-    float s[G][kSteps];
+    for (int i = 0; i < STEPS; ++i)
 #pragma unroll
-    for (int i = 0; i < kSteps; ++i) {
+      for (int v = 0; v < VPL; ++v) vx[i][v].raw = load_stream(vp + i * (kRPW * RP) + v * kLPR);
+
+    float s[G][STEPS];
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i) {
       float bl = 0.f;
       if constexpr (HAS_BIAS) bl = bx[i] * 1.4426950408889634f;
 #pragma unroll
-      for (int g = 0; g < G; ++g) s[g][i] = fmaf(row_sum<LPR>(kx[i].dot(qv[g])), a.scale_log2e, bl);
+      for (int g = 0; g < G; ++g) {
+        float d = kx[i][0].dot(qv[g][0]);
+#pragma unroll
+        for (int v = 1; v < VPL; ++v) d += kx[i][v].dot(qv[g][v]);
+        s[g][i] = fmaf(row_sum(d), a.scale_log2e, bl);
+      }
     }
 
     const bool masked = nvalid < TILE;   // wave-uniform: only the partial tail block takes this path
     if (masked) {
 #pragma unroll
-      for (int i = 0; i < kSteps; ++i) {
-        const bool ok = (i * RPW + r) < nvalid;
+      for (int i = 0; i < STEPS; ++i) {
+        const bool ok = (i * kRPW + r) < nvalid;
 #pragma unroll
         for (int g = 0; g < G; ++g) s[g][i] = ok ? s[g][i] : NEG_INF;
-        if (!ok) vx[i].raw = make_uint4(0, 0, 0, 0);   // stale bytes beyond T must not reach the sum
+        if (!ok) {   // stale bytes beyond T must not reach the sum
+#pragma unroll
+          for (int v = 0; v < VPL; ++v) vx[i][v].raw = make_uint4(0, 0, 0, 0);
+        }
       }
     }
 
@@ -239,46 +264,50 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
     for (int g = 0; g < G; ++g) {
       float mt = s[g][0];
 #pragma unroll
-      for (int i = 1; i < kSteps; ++i) mt = fmaxf(mt, s[g][i]);
+      for (int i = 1; i < STEPS; ++i) mt = fmaxf(mt, s[g][i]);
       const float m_new = fmaxf(m[g], mt);
       const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
       const float alpha = fast_exp2(m[g] - m_use);
       m[g] = m_new;
       l[g] *= alpha;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
+      for (int e = 0; e < LE; ++e) acc[g][e] *= alpha;
 #pragma unroll
-      for (int i = 0; i < kSteps; ++i) s[g][i] = fast_exp2(s[g][i] - m_use);
+      for (int i = 0; i < STEPS; ++i) s[g][i] = fast_exp2(s[g][i] - m_use);
     }
 #pragma unroll
-    for (int i = 0; i < kSteps; ++i) {
-      float vf[EPL];
-      vx[i].widen(vf);
+    for (int i = 0; i < STEPS; ++i) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float p = s[g][i];
-        l[g] += p;
+      for (int g = 0; g < G; ++g) l[g] += s[g][i];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
+      for (int v = 0; v < VPL; ++v) {
+        float vf[EPL];
+        vx[i][v].widen(vf);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          const float p = s[g][i];
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[g][v * EPL + e] = fmaf(p, vf[e], acc[g][v * EPL + e]);
+        }
       }
     }
   }
 
-  // ---- merge the RPW row-group states of this wave (lane exchange) ----
+  // ---- merge the 8 row-group states of this wave (lane exchange) ----
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     float M = m[g];
 #pragma unroll
-    for (int off = LPR; off < kWave; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
+    for (int off = kLPR; off < kWave; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
     const float sc = (m[g] == NEG_INF) ? 0.f : fast_exp2(m[g] - M);
     float lg = l[g] * sc;
 #pragma unroll
-    for (int off = LPR; off < kWave; off <<= 1) lg += __shfl_xor(lg, off);
+    for (int off = kLPR; off < kWave; off <<= 1) lg += __shfl_xor(lg, off);
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) {
+    for (int e = 0; e < LE; ++e) {
       float x = acc[g][e] * sc;
 #pragma unroll
-      for (int off = LPR; off < kWave; off <<= 1) x += __shfl_xor(x, off);
+      for (int off = kLPR; off < kWave; off <<= 1) x += __shfl_xor(x, off);
       acc[g][e] = x;
     }
     m[g] = M;
@@ -288,7 +317,9 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
 #pragma unroll
     for (int g = 0; g < G; ++g) {
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) s_acc[wave][g][c * EPL + e] = acc[g][e];
+      for (int v = 0; v < VPL; ++v)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s_acc[wave][g][(v * kLPR + c) * EPL + e] = acc[g][v * EPL + e];
       if (c == 0) {
         s_m[wave][g] = m[g];
         s_l[wave][g] = l[g];
@@ -383,9 +414,9 @@ bool decode_supports_group(int g) {
 int decode_default_splits(const nosa_params& p) {
   const int units = p.batch * p.n_kv_heads;
   const int row_bytes = p.head_dim * (p.dtype == NOSA_DTYPE_F32 ? 4 : 2);
-  const int tile_tokens = (kWave * 16 / row_bytes) * kSteps;
+  const int tile_tokens = kRPW * (kLoads / (row_bytes / 128));
   const int tiles = p.k_blocks * (kBlockTokens / tile_tokens);
-  int s = (2048 + units - 1) / units;           // enough workgroups to cover 256 CUs several times
+  int s = (512 + units - 1) / units;            // two workgroups per CU keep HBM busy; fewer splits, less merging
   const int cap = tiles / kWaves > 1 ? tiles / kWaves : 1;   // at least one tile per wave
   if (s > cap) s = cap;
   if (s > NOSA_MAX_SPLITS) s = NOSA_MAX_SPLITS;

@@ -2,10 +2,10 @@
 // positions (Sec. 4 "Memory Layout and Block Selection"; Alg. 1 generate_load_positions), one
 // wavefront per unit, one launch for both, nothing read back by the host.
 //
-// Exact top-k without sorting: scores are mapped to order-preserving 32-bit keys held in LDS, and
-// the k-th largest key is found by a bitwise binary search (32 rounds of "how many keys >= x",
-// counted with wave ballots).  Keys above the threshold are taken; ties at the threshold are taken
-// in ascending block order, which realises "the lower index wins".  The query-aware pass runs
+// Exact top-k without sorting: scores are mapped to order-preserving 32-bit keys held in registers
+// (block r*64 + lane in register r of a lane), and the k-th largest key is found by a bitwise
+// binary search (32 rounds of "how many keys >= x", counted with wave ballots on the scalar unit).
+// Keys above the threshold are taken; ties at the threshold are taken in ascending block order, which realises "the lower index wins".  The query-aware pass runs
 // first, its winners are removed, then the query-agnostic pass fills the rest of the budget.
 // Gamma(t) is emitted in ascending order by a ballot prefix scan over the selection flags; the
 // same scan yields the missed blocks, a second one over the slots yields the victims.
@@ -26,11 +26,13 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
   return __popcll(mask & ((1ull << lane) - 1ull));
 }
 
-// Marks the `want` largest eligible keys (key != 0) of keys[0..n) in flags[] with `tag`, ties to
-// the lower index, and zeroes the winners in `other` so that the next pass skips them.
-// All lanes of the wave call this with the same arguments.  Returns the number taken.
-__device__ int take_top(const uint32_t* keys, uint32_t* other, uint8_t* flags, int n, int want, int n_eligible,
-                        uint8_t tag, int lane) {
+// Marks the `want` largest eligible keys (key != 0) held in registers -- lane `lane`, register r
+// holds block r*64 + lane -- in flags[] with `tag`, ties to the lower block index, and zeroes the
+// winners in `other` so that the next pass skips them.  All lanes of the wave call this with the
+// same arguments.  Returns the number taken.
+template <int R, bool HAS_OTHER>
+__device__ __forceinline__ int take_top(uint32_t (&keys)[R], uint32_t (&other)[R], uint8_t* flags, int want,
+                                        int n_eligible, uint8_t tag, int lane) {
   if (want <= 0 || n_eligible <= 0) return 0;
   uint32_t thr = 1;   // every eligible key is >= thr
   if (want < n_eligible) {
@@ -38,11 +40,8 @@ __device__ int take_top(const uint32_t* keys, uint32_t* other, uint8_t* flags, i
     for (int bit = 31; bit >= 0; --bit) {
       const uint32_t cand = prefix | (1u << bit);
       int cnt = 0;
-      for (int base = 0; base < n; base += kWave) {
-        const int J = base + lane;
-        const bool ge = J < n && keys[J] >= cand;
-        cnt += __popcll(__ballot(ge));
-      }
+#pragma unroll
+      for (int r = 0; r < R; ++r) cnt += (int)__popcll(__ballot(keys[r] >= cand));
       if (cnt >= want) prefix = cand;
     }
     thr = prefix;   // the want-th largest key
@@ -50,22 +49,20 @@ __device__ int take_top(const uint32_t* keys, uint32_t* other, uint8_t* flags, i
     want = n_eligible;
   }
   int above = 0;
-  for (int base = 0; base < n; base += kWave) {
-    const int J = base + lane;
-    above += __popcll(__ballot(J < n && keys[J] > thr));
-  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) above += (int)__popcll(__ballot(keys[r] > thr));
   int ties_left = want - above;
-  for (int base = 0; base < n; base += kWave) {
-    const int J = base + lane;
-    const uint32_t k = J < n ? keys[J] : 0u;
-    const bool gt = k > thr && k != 0u;
-    const bool eq = k == thr && k != 0u;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const uint32_t k = keys[r];
+    const bool gt = k > thr;            // thr >= 1, so ineligible keys (0) never pass
+    const bool eq = k == thr;
     const uint64_t eqm = __ballot(eq);
     const bool take = gt || (eq && lanes_below(eqm, lane) < ties_left);
     ties_left -= min(ties_left, (int)__popcll(eqm));
     if (take) {
-      flags[J] = tag;
-      if (other) other[J] = 0u;
+      flags[r * kWave + lane] = tag;
+      if constexpr (HAS_OTHER) other[r] = 0u;
     }
   }
   return want;
@@ -84,13 +81,13 @@ struct SelectArgs {
   int n_kv_heads, max_blocks, k_blocks, kq_blocks, sink_blocks, window_blocks, gpu_slots;
 };
 
+// R = ceil(max_blocks / 64): candidate keys per lane, register resident.
+template <int R>
 __global__ __launch_bounds__(kWave) void select_kernel(const SelectArgs a) {
   extern __shared__ unsigned char smem[];
-  uint32_t* key_q = (uint32_t*)smem;                    // [max_blocks]
-  uint32_t* key_e = key_q + a.max_blocks;               // [max_blocks]
-  int32_t* miss = (int32_t*)(key_e + a.max_blocks);     // [K]
+  int32_t* miss = (int32_t*)smem;                       // [K]
   int32_t* victim = miss + a.k_blocks;                  // [K]
-  uint8_t* flags = (uint8_t*)(victim + a.k_blocks);     // [max_blocks] 0 none, 1 forced, 2 query-aware, 3 query-agnostic
+  uint8_t* flags = (uint8_t*)(victim + a.k_blocks);     // [R*64] 0 none, 1 forced, 2 query-aware, 3 query-agnostic
 
   const int unit = blockIdx.x;
   const int b = unit / a.n_kv_heads;
@@ -105,22 +102,23 @@ __global__ __launch_bounds__(kWave) void select_kernel(const SelectArgs a) {
 
   // forced blocks and candidate keys
   const int win_lo = N - a.window_blocks;
-  for (int J = lane; J < N; J += kWave) {
-    const bool forced = J < a.sink_blocks || J >= win_lo;
+  uint32_t key_q[R], key_e[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int J = r * kWave + lane;
+    const bool forced = J < N && (J < a.sink_blocks || J >= win_lo);
     const bool cand = !forced && J < Nc;
     flags[J] = forced ? 1 : 0;
-    key_q[J] = cand ? order_key(sq[J]) : 0u;
-    key_e[J] = cand ? order_key(se[J]) : 0u;
+    key_q[r] = cand ? order_key(sq[J]) : 0u;
+    key_e[r] = cand ? order_key(se[J]) : 0u;
   }
-  __syncthreads();
   const int nF = min(N, a.sink_blocks + a.window_blocks);
   const int nD = max(0, min(Nc, win_lo) - a.sink_blocks);
 
-  const int kq = take_top(key_q, key_e, flags, Nc, a.kq_blocks, nD, 2, lane);
-  __syncthreads();
+  const int kq = take_top<R, true>(key_q, key_e, flags, a.kq_blocks, nD, 2, lane);
   int ke = K - nF - a.kq_blocks;
   ke = max(0, min(ke, nD - kq));
-  take_top(key_e, nullptr, flags, Nc, ke, nD - kq, 3, lane);
+  take_top<R, false>(key_e, key_e, flags, ke, nD - kq, 3, lane);
   __syncthreads();
 
   // Gamma(t) ascending; misses = selected blocks without a slot
@@ -188,10 +186,18 @@ int launch_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const
   const nosa_params& p = ctx->p;
   SelectArgs a{sq_blk, se_blk, n_tokens, sel_idx, n_sel, slot_of_block, block_of_slot, load_list, n_load,
                p.n_kv_heads, p.max_blocks, p.k_blocks, p.kq_blocks, p.sink_blocks, p.window_blocks, p.gpu_slots};
-  const size_t smem = (size_t)p.max_blocks * 8 + (size_t)p.k_blocks * 8 + (size_t)p.max_blocks;
-  NOSA_REQUIRE(ctx, smem <= 64 * 1024, NOSA_ESHAPE, "selection needs %zu bytes of LDS (max 65536)", smem);
+  const int regs = (p.max_blocks + kWave - 1) / kWave;
+  const int R = regs <= 8 ? 8 : regs <= 16 ? 16 : regs <= 32 ? 32 : 64;
+  NOSA_REQUIRE(ctx, regs <= 64, NOSA_ESHAPE, "selection supports at most %d blocks per unit", kMaxSelectBlocks);
+  const size_t smem = (size_t)p.k_blocks * 8 + (size_t)R * kWave;
+  const dim3 grid(ctx->units), block(kWave);
   TimedLaunch tl(ctx, NOSA_KERNEL_SELECT, ctx->main);
-  hipLaunchKernelGGL(select_kernel, dim3(ctx->units), dim3(kWave), smem, ctx->main, a);
+  switch (R) {
+    case 8: hipLaunchKernelGGL(select_kernel<8>, grid, block, smem, ctx->main, a); break;
+    case 16: hipLaunchKernelGGL(select_kernel<16>, grid, block, smem, ctx->main, a); break;
+    case 32: hipLaunchKernelGGL(select_kernel<32>, grid, block, smem, ctx->main, a); break;
+    default: hipLaunchKernelGGL(select_kernel<64>, grid, block, smem, ctx->main, a); break;
+  }
   NOSA_HIP(ctx, hipGetLastError());
   return NOSA_OK;
 }
