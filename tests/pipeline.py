@@ -153,3 +153,95 @@ def run_parity(w: Workload, seed: int, steps: int, device="cuda:0", overlap=True
                 assert pb[b, h, s].tobytes() == ol.hb[b, h, J].tobytes()
     ctx.close()
     return records
+
+
+def run_fullsize_sampled(w: Workload, seed: int, steps: int, n_samples: int, device="cuda:0", margin=1e-3):
+    """A workload at its full size, in the launch configuration ``bench.py`` times (default splits,
+    fetch on the side stream, cold start through the real path), checked two ways:
+
+    * sampled units: each is re-run by the oracle as a one-unit problem on the same bytes, with its
+      residency state carried along; Gamma, miss count and the attention rows must match;
+    * all units: properties that hold at any size (Gamma ascending and unique, forced blocks inside,
+      miss count <= Kq after the first step, maps inverse to each other, finite outputs).
+    """
+    import paper_2510_13602_amd as nosa
+    from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+
+    print(f"fullsize {w.name}: drawing the layer on the GPU", flush=True)
+    layer = make_layer(w, seed, 0, device=device)
+    hk, hv, hb = pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"])
+    del layer
+    torch.cuda.empty_cache()
+    ctx = nosa.Nosa(gpu_params(w), device=device)
+    gl = LayerCache(ctx, hk, hv, hb, torch.full((w.batch,), w.context, dtype=torch.int32))
+    gl.rebuild_pooled()
+    gl.pool_k.fill_(float("nan")); gl.pool_v.fill_(float("nan")); gl.pool_bias.fill_(float("nan"))
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(seed + 99)
+    units = [(0, 0), (w.batch - 1, w.n_kv_heads - 1)]
+    while len(units) < n_samples:
+        u = (int(rng.integers(w.batch)), int(rng.integers(w.n_kv_heads)))
+        if u not in units:
+            units.append(u)
+    G = w.group
+    w1 = w.replace(batch=1, n_q_heads=G, n_kv_heads=1)
+    n1 = np.array([w.context], np.int32)
+    oracles = {}
+    for (b, h) in units:
+        ol = OracleLayer(w1, to_np(hk[b:b + 1, h:h + 1]), to_np(hv[b:b + 1, h:h + 1]), to_np(hb[b:b + 1, h:h + 1]), n1)
+        assert to_np(gl.k_pooled[b:b + 1, h:h + 1]).tobytes() == ol.kc.tobytes()     # the library's pooled keys
+        assert to_np(gl.se_pooled[b:b + 1, h:h + 1]).tobytes() == ol.sec.tobytes()
+        ol.pk[...] = 0x7fc0 if ol.pk.dtype == np.uint16 else np.nan
+        ol.pv[...] = 0x7fc0 if ol.pv.dtype == np.uint16 else np.nan
+        ol.pb[...] = np.nan
+        oracles[(b, h)] = ol
+    qs = QueryStream(w, seed, 0, device=device)
+    N, Nc = w.max_blocks, w.context // w.block_size
+    forced = sorted(set(range(min(w.sink_blocks, N))) | set(range(max(0, N - w.window_blocks), N)))
+    worst = 0.0
+    for t in range(steps):
+        d = qs.draw(t, 0)
+        for r in range(1, 9):                         # margin rule on the sampled units only
+            q = d["q32"].to(w.torch_dtype)
+            bad = []
+            for (b, h), ol in oracles.items():
+                gap = query_margin(w1, ol.scores(to_np(q[b:b + 1, h * G:(h + 1) * G]))[0], n1)[0, 0]
+                if gap < margin:
+                    bad.append((b, h))
+            if not bad:
+                break
+            alt = qs.draw(t, r)
+            for b, h in bad:
+                for key in ("q32", "x", "m"):
+                    if d[key] is not None:
+                        d[key][b, h * G:(h + 1) * G] = alt[key][b, h * G:(h + 1) * G]
+        q = qs.commit(d)
+        out = gl.step(q)
+        torch.cuda.synchronize()
+        sel, n_sel, n_load = gl.sel_idx.cpu().numpy(), gl.n_sel.cpu().numpy(), gl.n_load.cpu().numpy()
+        sob, bos = gl.slot_of_block.cpu().numpy(), gl.block_of_slot.cpu().numpy()
+        got = out.double().cpu().numpy()
+        # properties over all units
+        assert np.isfinite(got).all()
+        assert (n_sel == min(w.k_blocks, N)).all()
+        assert (np.diff(sel, axis=-1) > 0).all() and sel.min() >= 0 and sel.max() < N
+        assert all((sel == J).any(-1).all() for J in forced)
+        if t == 0:
+            assert (n_load == w.k_blocks).all()
+        elif w.gpu_slots == w.k_blocks:
+            assert n_load.max() <= w.kq_blocks
+        slots = np.take_along_axis(sob, sel, axis=-1)
+        assert (slots >= 0).all() and (np.take_along_axis(bos, slots, axis=-1) == sel).all()
+        assert (np.sort(slots, axis=-1)[..., 1:] != np.sort(slots, axis=-1)[..., :-1]).all()
+        # sampled units against the oracle
+        for (b, h), ol in oracles.items():
+            ref = ol.step(to_np(q[b:b + 1, h * G:(h + 1) * G]))
+            assert (sel[b, h] == ref["sel"][0, 0]).all(), f"step {t} unit {(b, h)}: selected blocks differ"
+            assert n_load[b, h] == ref["n_load"][0, 0], f"step {t} unit {(b, h)}: miss count differs"
+            err = float(np.abs(got[b, h * G:(h + 1) * G] - ref["out"][0]).max())
+            worst = max(worst, err)
+            assert err <= out_tol(w.dtype), f"step {t} unit {(b, h)}: max abs err {err}"
+        print(f"fullsize {w.name} step {t}: n_load mean {n_load.mean():.2f} max {n_load.max()}, worst err so far {worst:.2e}", flush=True)
+    ctx.close()
+    return worst

@@ -65,6 +65,8 @@ DECODE_CASES = [
     ("bf16", 128, 1, 1, 64, 70, 3, None, True),         # group 1
     ("fp32", 64, 12, 1, 6, 9, 7, None, True),           # group 12
     ("bf16", 64, 16, 1, 6, 9, 7, 4, True),              # group 16
+    ("bf16", 64, 2, 1, 256, 259, 5, None, True),        # the largest supported selection (K = 256)
+    ("fp32", 128, 4, 1, 3, 2, 1, 16, True),             # more splits than tiles: empty splits merge cleanly
 ]
 
 
