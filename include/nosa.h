@@ -158,6 +158,23 @@ int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const v
 int nosa_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const int32_t* n_tokens,
                      void* k_pooled, float* se_pooled);
 
+/* Appends the current token of every unit (Alg. 1: the cache engine is updated before Stage 1).
+ * k_new, v_new [B,Hkv,d] dtype, b_new [B,Hkv] fp32, all dev.  Token t = n_tokens[b] goes to block
+ * J = t / n_b, row t % n_b of the host pool (written by the GPU over the host link) and, when block J
+ * has a slot, to that slot.  A token that opens a new block first gives the block a slot: the lowest
+ * empty slot, else the slot of the resident block with the smallest se_blk (block-level importance
+ * as written by the last nosa_block_score; ties: lower slot) among blocks that are neither sink
+ * blocks nor among the last max(Nw, 2) blocks before J; if there is none the block stays
+ * non-resident and the next nosa_select lists it as a miss.  Evicting the least important candidate
+ * keeps the per-step fetch bound of Theorem 1 across block boundaries.  Then every sub-block that
+ * this token completes gets its pooled key and pooled importance (same arithmetic as
+ * nosa_pool_blocks, read back from the host pool), and n_tokens[b] is incremented.  Tokens beyond
+ * max_blocks * n_b are ignored.  Not part of the timed path.                                      */
+int nosa_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float* b_new,
+                void* pool_k, void* pool_v, float* pool_bias, void* host_k, void* host_v, float* host_bias,
+                void* k_pooled, float* se_pooled, const float* se_blk, int32_t* n_tokens,
+                int32_t* slot_of_block, int32_t* block_of_slot);
+
 /* ---- per-kernel timing for benchmarks --------------------------------------------------------*/
 
 #define NOSA_KERNEL_SCORE 0

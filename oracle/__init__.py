@@ -233,3 +233,27 @@ def params_from_workload(w, **over) -> Params:
               pool_kernel=w.pool_kernel, pool_stride=w.pool_stride)
     kw.update(over)
     return Params(**kw)
+
+
+def append(p: Params, k_new, v_new, b_new, pool_k, pool_v, pool_bias, host_k, host_v, host_bias, se_blk,
+           n_tokens, slot_of_block, block_of_slot) -> None:
+    """Append one token per unit to the cache (host pool, and the GPU slot of its block); in place."""
+    B, H, d, nb = p.batch, p.n_kv_heads, p.head_dim, p.block_size
+    _check(k_new, (B, H, d), p.np_dtype, "k_new")
+    _check(v_new, (B, H, d), p.np_dtype, "v_new")
+    _check(b_new, (B, H), np.float32, "b_new")
+    _check(pool_k, (B, H, p.gpu_slots, nb, d), p.np_dtype, "pool_k")
+    _check(pool_v, (B, H, p.gpu_slots, nb, d), p.np_dtype, "pool_v")
+    _check(pool_bias, (B, H, p.gpu_slots, nb), np.float32, "pool_bias")
+    _check(host_k, (B, H, p.max_blocks, nb, d), p.np_dtype, "host_k")
+    _check(host_v, (B, H, p.max_blocks, nb, d), p.np_dtype, "host_v")
+    _check(host_bias, (B, H, p.max_blocks, nb), np.float32, "host_bias")
+    se_blk = np.ascontiguousarray(se_blk, dtype=np.float64)
+    _check(se_blk, (B, H, p.max_blocks), np.float64, "se_blk")
+    _check(n_tokens, (B,), np.int32, "n_tokens")
+    _check(slot_of_block, (B, H, p.max_blocks), np.int32, "slot_of_block")
+    _check(block_of_slot, (B, H, p.gpu_slots), np.int32, "block_of_slot")
+    pc = p.c()
+    lib().oracle_append(ctypes.byref(pc), _ptr(k_new), _ptr(v_new), _ptr(b_new), _ptr(pool_k), _ptr(pool_v),
+                        _ptr(pool_bias), _ptr(host_k), _ptr(host_v), _ptr(host_bias), _ptr(se_blk), _ptr(n_tokens),
+                        _ptr(slot_of_block), _ptr(block_of_slot))

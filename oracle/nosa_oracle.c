@@ -20,6 +20,7 @@
  *   oracle_fetch         Sec. 4 "Offloading Communication": copy missed blocks host -> slot
  *   oracle_attention     the biased attention output of Sec. 3.1 "Attention Calculation"
  *                        (exp(b_j) exp(q k_j + m_j) normalised), restricted to Gamma(t)
+ *   oracle_append        the cache update that precedes Stage 1 in Alg. 1, for a growing context
  *
  * Readings taken where the paper is silent (each is a parameter or a stated rule):
  *   - pooling windows are half open, [j*ls, j*ls+lk): exactly lk terms;
@@ -360,4 +361,61 @@ int oracle_attention(const oracle_params *p, const void *q, const void *pool_k, 
     free(z);
   }
   return bad;
+}
+
+/* ---- growing context: append one token per unit (Alg. 1 cache update before Stage 1) ---------
+ * k_new, v_new [B,Hkv,d] (dtype), b_new [B,Hkv] fp32.  Token t = n_tokens[b] of every unit of batch
+ * element b is written to the host pool (block J = t / nb, row t % nb) and, if block J has a slot,
+ * to that slot.  When the token opens a new block (row 0) the block is given a slot first: the lowest
+ * empty slot, else the slot whose block has the smallest block-level importance se_blk among the
+ * resident blocks that are neither sink blocks nor among the last max(Nw, 2) blocks before J (ties:
+ * lower slot); if there is none the block simply stays non-resident and is fetched like any miss.
+ * Evicting the least important resident candidate keeps the Ke best-by-importance candidates
+ * resident, which is what the proof of Theorem 1 needs for the per-step fetch bound.
+ * n_tokens is incremented once per batch element at the end.  Tokens beyond the table capacity
+ * (t >= max_blocks * nb) are ignored.  Pooled arrays are not touched here (see oracle_pool).      */
+void oracle_append(const oracle_params *p, const void *k_new, const void *v_new, const float *b_new,
+                   void *pool_k, void *pool_v, float *pool_bias, void *host_k, void *host_v, float *host_bias,
+                   const double *se_blk, int32_t *n_tokens, int32_t *slot_of_block, int32_t *block_of_slot) {
+  const int nb = p->block_size, d = p->head_dim, C = p->gpu_slots;
+  const size_t es = p->dtype == 0 ? 4 : 2;
+  const size_t rowb = (size_t)d * es;
+  const int units = p->batch * p->n_kv_heads;
+  for (int u = 0; u < units; ++u) {
+    const int b = u / p->n_kv_heads;
+    const int t = n_tokens[b];
+    if (t >= p->max_blocks * nb) continue;
+    const int J = t / nb, row = t % nb;
+    int32_t *sob = slot_of_block + (int64_t)u * p->max_blocks;
+    int32_t *bos = block_of_slot + (int64_t)u * C;
+    const size_t hrow = ((size_t)u * p->max_blocks + J) * nb + row;
+    memcpy((char *)host_k + hrow * rowb, (const char *)k_new + (size_t)u * rowb, rowb);
+    memcpy((char *)host_v + hrow * rowb, (const char *)v_new + (size_t)u * rowb, rowb);
+    host_bias[hrow] = b_new[u];
+    if (row == 0 && sob[J] < 0) {
+      int best = -1;
+      for (int s = 0; s < C && best < 0; ++s) if (bos[s] < 0) best = s;
+      if (best < 0) {
+        const int protect = p->window_blocks > 2 ? p->window_blocks : 2;
+        for (int s = 0; s < C; ++s) {
+          const int Jp = bos[s];
+          if (Jp < p->sink_blocks || Jp > J - protect) continue;
+          if (best < 0 || se_blk[(int64_t)u * p->max_blocks + Jp] < se_blk[(int64_t)u * p->max_blocks + bos[best]]) best = s;
+        }
+      }
+      if (best >= 0) {
+        if (bos[best] >= 0) sob[bos[best]] = -1;
+        bos[best] = J;
+        sob[J] = best;
+      }
+    }
+    if (sob[J] >= 0) {
+      const size_t prow = ((size_t)u * C + sob[J]) * nb + row;
+      memcpy((char *)pool_k + prow * rowb, (const char *)k_new + (size_t)u * rowb, rowb);
+      memcpy((char *)pool_v + prow * rowb, (const char *)v_new + (size_t)u * rowb, rowb);
+      pool_bias[prow] = b_new[u];
+    }
+  }
+  for (int b = 0; b < p->batch; ++b)
+    if (n_tokens[b] < p->max_blocks * nb) n_tokens[b] += 1;
 }

@@ -23,7 +23,7 @@ MAX_SPLITS = 16
 EXPORTS = [
     "nosa_validate_params", "nosa_create", "nosa_destroy", "nosa_workspace_bytes", "nosa_set_workspace",
     "nosa_set_splits", "nosa_get_splits", "nosa_set_overlap", "nosa_last_error", "nosa_block_score",
-    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_timing_enable",
+    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_append", "nosa_timing_enable",
     "nosa_timing_read",
 ]
 
@@ -71,6 +71,7 @@ def load_library() -> ctypes.CDLL:
     lib.nosa_fetch.argtypes = [vp, vp, vp, fp, vp, vp, fp, i32p, i32p]
     lib.nosa_sparse_decode.argtypes = [vp, vp, vp, vp, fp, i32p, i32p, i32p, i32p, vp, fp]
     lib.nosa_pool_blocks.argtypes = [vp, vp, fp, i32p, vp, fp]
+    lib.nosa_append.argtypes = [vp] + [vp] * 15
     lib.nosa_timing_enable.argtypes = [vp, ctypes.c_int]
     lib.nosa_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     for name in EXPORTS:
@@ -242,3 +243,25 @@ class Nosa:
             _dev(n_tokens, torch.int32, (B,), "n_tokens"),
             _dev(k_pooled, self.tdtype, (B, H, p.n_sub_max, p.head_dim), "k_pooled"),
             _dev(se_pooled, torch.float32, (B, H, p.n_sub_max), "se_pooled")))
+
+    def nosa_append(self, k_new, v_new, b_new, pool_k, pool_v, pool_bias, host_k, host_v, host_bias, k_pooled,
+                    se_pooled, se_blk, n_tokens, slot_of_block, block_of_slot) -> None:
+        p, B, H = self.p, self._B, self._H
+        kv_host = (B, H, p.max_blocks, p.block_size, p.head_dim)
+        kv_pool = (B, H, p.gpu_slots, p.block_size, p.head_dim)
+        for t, name in ((host_k, "host_k"), (host_v, "host_v"), (host_bias, "host_bias")):
+            if not (t.is_cuda or t.is_pinned()):
+                raise ValueError(f"{name} must be pinned host memory (or device memory)")
+        self._check(self.lib.nosa_append(
+            self._ctx, _dev(k_new, self.tdtype, (B, H, p.head_dim), "k_new"), _dev(v_new, self.tdtype, (B, H, p.head_dim), "v_new"),
+            _dev(b_new, torch.float32, (B, H), "b_new"),
+            _dev(pool_k, self.tdtype, kv_pool, "pool_k"), _dev(pool_v, self.tdtype, kv_pool, "pool_v"),
+            _dev(pool_bias, torch.float32, kv_pool[:4], "pool_bias"),
+            _raw(host_k, self.tdtype, kv_host, "host_k"), _raw(host_v, self.tdtype, kv_host, "host_v"),
+            _raw(host_bias, torch.float32, kv_host[:4], "host_bias"),
+            _dev(k_pooled, self.tdtype, (B, H, p.n_sub_max, p.head_dim), "k_pooled"),
+            _dev(se_pooled, torch.float32, (B, H, p.n_sub_max), "se_pooled"),
+            _dev(se_blk, torch.float32, (B, H, p.max_blocks), "se_blk"),
+            _dev(n_tokens, torch.int32, (B,), "n_tokens"),
+            _dev(slot_of_block, torch.int32, (B, H, p.max_blocks), "slot_of_block"),
+            _dev(block_of_slot, torch.int32, (B, H, p.gpu_slots), "block_of_slot")))

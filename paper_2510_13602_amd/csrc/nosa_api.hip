@@ -278,6 +278,22 @@ int nosa_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const i
   return nosa::launch_pool_blocks(ctx, keys, bias, n_tokens, k_pooled, se_pooled);
 }
 
+int nosa_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float* b_new, void* pool_k, void* pool_v,
+                float* pool_bias, void* host_k, void* host_v, float* host_bias, void* k_pooled, float* se_pooled,
+                const float* se_blk, int32_t* n_tokens, int32_t* slot_of_block, int32_t* block_of_slot) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, k_new && v_new && b_new && pool_k && pool_v && pool_bias && host_k && host_v && host_bias && se_blk &&
+                        n_tokens && slot_of_block && block_of_slot,
+               NOSA_EINVAL, "nosa_append: NULL argument");
+  NOSA_REQUIRE(ctx, ctx->p.n_sub_max == 0 || (k_pooled && se_pooled), NOSA_EINVAL, "nosa_append: k_pooled / se_pooled is NULL");
+  if (ctx->fetch_pending) {   // the gather of the previous step may still be writing slots
+    NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, ctx->ev_fetch, 0));
+    ctx->fetch_pending = false;
+  }
+  return nosa::launch_append(ctx, k_new, v_new, b_new, pool_k, pool_v, pool_bias, host_k, host_v, host_bias, k_pooled,
+                             se_pooled, se_blk, n_tokens, slot_of_block, block_of_slot);
+}
+
 int nosa_timing_enable(nosa_ctx* ctx, int on) {
   NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
   ctx->timing = on != 0;

@@ -36,8 +36,8 @@ class LayerCache:
         self.block_of_slot = torch.full((B, H, C), -1, dtype=torch.int32, device=dev)
         self.k_pooled = torch.zeros((B, H, p.n_sub_max, d), dtype=dt, device=dev)
         self.se_pooled = torch.zeros((B, H, p.n_sub_max), dtype=torch.float32, device=dev)
-        self.sq_blk = torch.empty((B, H, p.max_blocks), dtype=torch.float32, device=dev)
-        self.se_blk = torch.empty((B, H, p.max_blocks), dtype=torch.float32, device=dev)
+        self.sq_blk = torch.full((B, H, p.max_blocks), float("-inf"), dtype=torch.float32, device=dev)
+        self.se_blk = torch.full((B, H, p.max_blocks), float("-inf"), dtype=torch.float32, device=dev)
         self.sel_idx = torch.empty((B, H, p.k_blocks), dtype=torch.int32, device=dev)
         self.n_sel = torch.empty((B, H), dtype=torch.int32, device=dev)
         self.load_list = torch.empty((B, H, p.k_blocks, 2), dtype=torch.int32, device=dev)
@@ -63,6 +63,12 @@ class LayerCache:
                 self.pool_k[b, h, s.to(dev)] = self.host_k[b, h, blk].to(dev)
                 self.pool_v[b, h, s.to(dev)] = self.host_v[b, h, blk].to(dev)
                 self.pool_bias[b, h, s.to(dev)] = self.host_bias[b, h, blk].to(dev)
+
+    def append(self, k_new: torch.Tensor, v_new: torch.Tensor, b_new: torch.Tensor) -> None:
+        """Appends the current token of every unit (cache update that precedes Stage 1 in Alg. 1)."""
+        self.nosa.nosa_append(k_new, v_new, b_new, self.pool_k, self.pool_v, self.pool_bias, self.host_k, self.host_v,
+                              self.host_bias, self.k_pooled, self.se_pooled, self.se_blk, self.n_tokens,
+                              self.slot_of_block, self.block_of_slot)
 
     # the four calls of one decode step, in the order of Alg. 1
     def score(self, q: torch.Tensor) -> None:

@@ -245,3 +245,60 @@ def run_fullsize_sampled(w: Workload, seed: int, steps: int, n_samples: int, dev
         print(f"fullsize {w.name} step {t}: n_load mean {n_load.mean():.2f} max {n_load.max()}, worst err so far {worst:.2e}", flush=True)
     ctx.close()
     return worst
+
+
+def run_growing(w: Workload, seed: int, steps: int, device="cuda:0", margin=1e-3, check_every=1):
+    """Growing context: every step after the first appends one token per unit (key, value, bias)
+    before scoring, on both sides; all state (pool, maps, pooled arrays, token counts) is compared.
+    Also asserts the fetch bound n_load <= Kq at every step after the first, block boundaries included.
+    """
+    import paper_2510_13602_amd as nosa
+    from nosa_inputs import append_token
+    from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+
+    assert w.generated >= steps
+    layer = make_layer(w, seed, 0)
+    n_tok = np.full((w.batch,), w.context, np.int32)
+    ol = OracleLayer(w, to_np(layer["host_k"]).copy(), to_np(layer["host_v"]).copy(), to_np(layer["host_bias"]).copy(), n_tok)
+    ctx = nosa.Nosa(gpu_params(w), device=device)
+    gl = LayerCache(ctx, pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"]),
+                    torch.from_numpy(n_tok))
+    gl.rebuild_pooled()
+    qs = QueryStream(w, seed, 0)
+    prev_se = np.full((w.batch, w.n_kv_heads, w.max_blocks), -np.inf)
+    boundary_loads, worst = [], 0.0
+    for t in range(steps):
+        if t > 0:
+            tok = append_token(w, seed, 0, t)
+            oracle.append(ol.p, to_np(tok["k_new"]), to_np(tok["v_new"]), to_np(tok["b_new"]), ol.pk, ol.pv, ol.pb,
+                          ol.hk, ol.hv, ol.hb, prev_se, ol.n_tok, ol.sob, ol.bos)
+            ol.kc, ol.sec = oracle.pool(ol.p, ol.hk, ol.hb, ol.n_tok)
+            gl.append(tok["k_new"].to(device), tok["v_new"].to(device), tok["b_new"].to(device))
+        q, _ = draw_with_margin(w, qs, ol, t, margin)
+        ref = ol.step(to_np(q))
+        prev_se = ref["se"]
+        out = gl.step(q.to(device))
+        torch.cuda.synchronize()
+        assert (gl.n_tokens.cpu().numpy() == ol.n_tok).all(), f"step {t}: token counts differ"
+        assert (gl.sel_idx.cpu().numpy() == ref["sel"]).all(), f"step {t}: selected blocks differ"
+        assert (gl.n_load.cpu().numpy() == ref["n_load"]).all(), f"step {t}: miss counts differ"
+        assert (gl.load_list.cpu().numpy() == ref["load_list"]).all()
+        assert (gl.slot_of_block.cpu().numpy() == ol.sob).all() and (gl.block_of_slot.cpu().numpy() == ol.bos).all()
+        if t > 0 and w.gpu_slots == w.k_blocks:
+            assert ref["n_load"].max() <= w.kq_blocks, f"step {t}: fetch bound broken ({ref['n_load'].max()})"
+        if (w.context + t) % w.block_size == 0:
+            boundary_loads.append(int(ref["n_load"].max()))
+        if t % check_every == 0 or (w.context + t) % w.block_size in (0, 1, w.block_size - 1):
+            assert to_np(gl.k_pooled).tobytes() == ol.kc.tobytes(), f"step {t}: pooled keys differ"
+            assert to_np(gl.se_pooled).tobytes() == ol.sec.tobytes(), f"step {t}: pooled importance differs"
+            got = out.double().cpu().numpy()
+            assert np.isfinite(got).all()
+            err = float(np.abs(got - ref["out"]).max())
+            worst = max(worst, err)
+            assert err <= out_tol(w.dtype), f"step {t}: max abs err {err}"
+    # the host pool received every appended token
+    torch.cuda.synchronize()
+    assert to_np(gl.host_k).tobytes() == ol.hk.tobytes() and to_np(gl.host_v).tobytes() == ol.hv.tobytes()
+    assert to_np(gl.host_bias).tobytes() == ol.hb.tobytes()
+    ctx.close()
+    return dict(worst=worst, boundary_loads=boundary_loads)

@@ -74,3 +74,20 @@ def test_8b_shaped_reduced_batch():
     w = CONFIGS["8b"].replace(batch=1)
     rec = run_parity(w, seed=0, steps=5)
     print("8b: n_load mean per step", [round(r["n_load_mean"], 2) for r in rec], flush=True)
+
+
+def test_long_generation_growing_context():
+    """Long-generation 8B-shaped: prompt 4096 (N = 64 = K, the first step is dense), then tokens are
+    appended one per step; 200 steps cross three block boundaries.  Batch cut to 2 for the oracle."""
+    from pipeline import run_growing
+    w = CONFIGS["longgen"].replace(batch=2, generated=200)
+    r = run_growing(w, seed=0, steps=200)
+    print("longgen: worst err", r["worst"], "n_load max at block boundaries", r["boundary_loads"], flush=True)
+    assert len(r["boundary_loads"]) == 4 and max(r["boundary_loads"][1:]) <= w.kq_blocks   # step 0 (cold) + 3 boundaries
+
+
+def test_growing_context_small_ragged_fp32():
+    """fp32, d64, group 4, K = 8, starting mid-block, two-stage pooling with several sub-blocks per block."""
+    from pipeline import run_growing
+    w = CONFIGS["tiny"].replace(context=64 * 20 + 50, generated=150, pool_kernel=32, pool_stride=16, batch=2)
+    run_growing(w, seed=3, steps=150)
