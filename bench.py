@@ -154,7 +154,7 @@ def main():
     # queries: one stream per host pool (the planted directions belong to the pool)
     streams = [QueryStream(w, args.seed, hl, device=dev) for hl in range(LH)]
     total = args.warmup + args.steps
-    n_q = 1 if args.resident else total + L
+    n_q = 1 if args.resident else 2 * total + L + 16
     queries = [[streams[hl].next(t) for t in range(n_q)] for hl in range(LH)]
 
     def q_of(l, i):
@@ -170,28 +170,48 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
 
-    ctx.timing_enable(not args.no_kernel_timing)
-    for k in range(5):
-        ctx.timing_read(k)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        j = args.warmup + i
-        layers[j % L].step(q_of(j % L, 1 + j))
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ctx.timing_enable(False)
-
     names = ["block_score", "select", "fetch", "sparse_decode", "combine"]
-    kern = {}
-    for k, name in enumerate(names):
-        ms, n = ctx.timing_read(k)
-        kern[name] = {"launches": n, "avg_us": (1e3 * ms / n) if n else None}
+    step_no = [args.warmup]
+
+    def timed_region(n_steps):
+        """n_steps steps between two synchronisations; returns (seconds, per-kernel mean durations)."""
+        ctx.timing_enable(not args.no_kernel_timing)
+        for k in range(5):
+            ctx.timing_read(k)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_steps):
+            j = step_no[0]
+            layers[j % L].step(q_of(j % L, 1 + j))
+            step_no[0] += 1
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ctx.timing_enable(False)
+        kern = {}
+        for k, name in enumerate(names):
+            ms, n = ctx.timing_read(k)
+            kern[name] = (1e3 * ms / n) if n else None
+        return dt, kern
+
+    # region 1 (the headline): library default -- gather on the side stream, attention over the resident
+    # blocks overlapping it.  region 2: the same steps with everything on one stream, so that every kernel
+    # runs alone; the roofline figure of the attention kernel is taken there.
+    dt, kern = timed_region(args.steps)
     loads = torch.stack([lc.n_load.float() for lc in layers[:min(L, args.steps)]])
     mean_load, max_load = float(loads.mean().item()), float(loads.max().item())
+    if args.resident or args.no_overlap:
+        dt_alone, kern_alone = dt, kern
+    else:
+        ctx.set_overlap(False)
+        for _ in range(min(8, args.warmup)):
+            j = step_no[0]
+            layers[j % L].step(q_of(j % L, 1 + j))
+            step_no[0] += 1
+        dt_alone, kern_alone = timed_region(args.steps)
+        ctx.set_overlap(True)
 
     units = w.units
-    dec_us = kern["sparse_decode"]["avg_us"]
+    dec_us = kern_alone["sparse_decode"]
     dec_bytes = decode_bytes_per_unit(w) * units
     achieved = dec_bytes / (dec_us * 1e-6) / 1e9 if dec_us else None
     peak = 8000.0
@@ -201,7 +221,7 @@ def main():
         with open(tfile) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
     blk_bytes = 2 * w.block_size * w.head_dim * w.elem_size + w.block_size * 4
-    fetch_us = kern["fetch"]["avg_us"]
+    fetch_us = kern["fetch"]
     line = {
         "metric": "sparse decode steps/sec (batch x KV heads x layer units) at fixed ctx",
         "value": units * args.steps / dt,
@@ -215,11 +235,14 @@ def main():
                    "kq_blocks": w.kq_blocks, "sink_blocks": w.sink_blocks, "window_blocks": w.window_blocks,
                    "gpu_slots": w.gpu_slots, "layers_cycled": L, "host_pools": LH, "splits": ctx.splits,
                    "fetch": "resident (no misses)" if args.resident else ("side stream" if not args.no_overlap else "main stream")},
-        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel", "achieved": achieved, "peak": peak, "unit": "GB/s",
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<bf16,128,4,false>" if w.name == "8b" else "decode_partial_kernel",
+                     "achieved": achieved, "peak": peak, "unit": "GB/s",
                      "frac": (achieved / peak) if achieved else None, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": dec_bytes, "avg_launch_us": dec_us},
+                     "algorithmic_bytes_per_launch": dec_bytes, "avg_launch_us": dec_us,
+                     "timed": f"{args.steps} steps with every kernel alone on one stream (second timed region)"},
         "cpu_baseline": None,
-        "kernels_avg_us": {k: v["avg_us"] for k, v in kern.items()},
+        "kernels_avg_us": kern,
+        "alone": {"ms_per_step": 1e3 * dt_alone / args.steps, "value": units * args.steps / dt_alone, "kernels_avg_us": kern_alone},
         "step_hbm_GBps": step_bytes_per_unit(w) * units * args.steps / dt / 1e9,
         "fetch": {"mean_blocks_per_unit": mean_load, "max_blocks_per_unit": max_load, "cold_start_blocks_per_unit": cold_loads,
                   "host_link_GBps": (mean_load * units * blk_bytes / (fetch_us * 1e-6) / 1e9) if fetch_us else None},

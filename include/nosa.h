@@ -97,9 +97,10 @@ int nosa_set_workspace(nosa_ctx* ctx, void* dev_ws, size_t bytes);
 int nosa_set_splits(nosa_ctx* ctx, int splits);
 int nosa_get_splits(const nosa_ctx* ctx);
 
-/* overlap = 1 (default): fetches run on the context's own stream and the attention over the
- * blocks that were already resident does not wait for them.  overlap = 0: everything is enqueued
- * on the main stream in call order (used to check that both orders give the same bits).          */
+/* overlap = 1 (default): fetches run on the context's own stream; a nosa_sparse_decode that follows
+ * a nosa_fetch first attends the selected blocks that are not in that fetch's load list, then waits
+ * for the fetch, attends the fetched blocks and merges.  overlap = 0: everything is enqueued on the
+ * main stream in call order (used to check that both orders give the same result).               */
 int nosa_set_overlap(nosa_ctx* ctx, int overlap);
 
 const char* nosa_last_error(const nosa_ctx* ctx); /* ctx may be NULL */

@@ -1,6 +1,7 @@
 // C-ABI entry points of libnosa: argument validation, context, stream ordering, timing.
 // Every entry point validates before it launches; the kernels live in the other files.
 #include <cmath>
+#include <cstdlib>
 #include <new>
 
 #include "nosa_internal.h"
@@ -123,6 +124,10 @@ int nosa_create(nosa_ctx** out, const nosa_params* p, void* main_stream) {
   ctx->scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
   ctx->main = (hipStream_t)main_stream;
   ctx->splits = nosa::decode_default_splits(*p);
+  if (const char* e = getenv("NOSA_FETCH_WGS")) {   // tuning knob for experiments
+    const int v = atoi(e);
+    if (v >= 1 && v <= 65535) ctx->fetch_wgs = v;
+  }
   auto bail = [&](const char* what, hipError_t e) {
     set_error(nullptr, NOSA_EHIP, "%s failed: %s", what, hipGetErrorString(e));
     nosa_destroy(ctx);
@@ -253,6 +258,8 @@ int nosa_fetch(nosa_ctx* ctx, const void* host_k, const void* host_v, const floa
   if (ctx->overlap) {
     NOSA_HIP(ctx, hipEventRecord(ctx->ev_fetch, ctx->side));
     ctx->fetch_pending = true;
+    ctx->pending_load_list = load_list;
+    ctx->pending_n_load = n_load;
   }
   return NOSA_OK;
 }
@@ -264,11 +271,17 @@ int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const v
   NOSA_REQUIRE(ctx, q && pool_k && pool_v && sel_idx && n_sel && slot_of_block && n_tokens && out, NOSA_EINVAL,
                "nosa_sparse_decode: NULL argument");
   NOSA_REQUIRE(ctx, ctx->splits == 1 || ctx->ws, NOSA_EINVAL, "nosa_sparse_decode: no workspace set (nosa_set_workspace)");
+  // A gather in flight: the blocks it is writing are the ones in its load list; everything else in
+  // the selection is already in place, so that part of the attention does not wait for it.
+  hipEvent_t wait = nullptr;
+  const int32_t *ll = nullptr, *nl = nullptr;
   if (ctx->fetch_pending) {
-    NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, ctx->ev_fetch, 0));
+    wait = ctx->ev_fetch;
+    ll = ctx->pending_load_list;
+    nl = ctx->pending_n_load;
     ctx->fetch_pending = false;
   }
-  return nosa::launch_decode(ctx, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse);
+  return nosa::launch_decode(ctx, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse, wait, ll, nl);
 }
 
 int nosa_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const int32_t* n_tokens,

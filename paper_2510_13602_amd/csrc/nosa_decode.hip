@@ -57,7 +57,11 @@ struct DecodeArgs {
   float* part_ml;  // [units][splits][G][2]  (m in log2 domain, l)
   void* out;
   float* lse;
+  const int32_t* load_list;   // phases 1 and 2: the (block, slot) pairs of the fetch in flight
+  const int32_t* n_load;
   int n_kv_heads, gpu_slots, k_blocks, max_blocks, splits;
+  int phase;         // 0: all selected blocks; 1: only blocks not in load_list; 2: only load_list, then merge
+  int merge_splits;  // phase 2: number of phase-1 partial results per unit to merge into the output
   float scale_log2e;
 };
 
@@ -138,8 +142,13 @@ __device__ __forceinline__ void store_out(void* out, size_t idx, float v, int dt
   }
 }
 
-template <int DT, int D, int G, bool HAS_BIAS>
+// OVERLAP = false: the plain kernel (phase 0).  OVERLAP = true: the two launches that bracket a
+// gather in flight (phase 1: resident blocks only; phase 2: fetched blocks, then the merge); a
+// separate instantiation so that profiles list the stand-alone kernel on its own.
+template <int DT, int D, int G, bool OVERLAP>
 __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeArgs a) {
+  const int phase = OVERLAP ? a.phase : 0;
+  const bool has_bias = a.pool_bias != nullptr;
   using V = Vec<DT>;
   constexpr int EPL = V::kElems;                 // elements per 16-byte load
   constexpr int RP = D / EPL;                    // row pitch in 16-byte vectors
@@ -157,8 +166,8 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
   __shared__ float s_l[kWaves][G];
   __shared__ float s_acc[kWaves][G][D];
 
-  const int unit = blockIdx.y;
-  const int split = blockIdx.x;
+  const int unit = blockIdx.x / a.splits;
+  const int split = blockIdx.x % a.splits;
   const int b = unit / a.n_kv_heads;
   const int h = unit % a.n_kv_heads;
   const int tid = threadIdx.x;
@@ -167,18 +176,51 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
   const int r = lane / kLPR;   // row-group within the wave
   const int c = lane % kLPR;   // 16-byte slice of a 128-byte line
 
-  const int n_sel = min(a.n_sel[unit], a.k_blocks);
   const int T = a.n_tokens[b];
-  for (int i = tid; i < n_sel; i += kThreads) {
-    const int J = a.sel_idx[(size_t)unit * a.k_blocks + i];
-    int slot = -1, valid = 0;
-    if (J >= 0 && J < a.max_blocks) {
-      slot = a.slot_of_block[(size_t)unit * a.max_blocks + J];
-      valid = min(kBlockTokens, T - J * kBlockTokens);
+  int n_sel;   // entries of the work table
+  if (phase == 2) {
+    // the blocks that were fetched for this step: (block, slot) pairs of the load list
+    n_sel = min(a.n_load[unit], a.k_blocks);
+    const int32_t* ll = a.load_list + (size_t)unit * a.k_blocks * 2;
+    const int n_all = min(a.n_sel[unit], a.k_blocks);
+    const int32_t* sel = a.sel_idx + (size_t)unit * a.k_blocks;
+    for (int i = tid; i < n_sel; i += kThreads) {
+      const int J = ll[2 * i], slot = ll[2 * i + 1];
+      int valid = (J >= 0 && J < a.max_blocks) ? min(kBlockTokens, T - J * kBlockTokens) : 0;
+      if (slot < 0 || slot >= a.gpu_slots) valid = 0;
+      // only blocks of the selection are attended (the selection is ascending)
+      int lo = 0, hi = n_all;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (sel[mid] < J) lo = mid + 1; else hi = mid;
+      }
+      if (!(lo < n_all && sel[lo] == J)) valid = 0;
+      s_slot[i] = slot;
+      s_valid[i] = valid;
     }
-    if (slot < 0 || slot >= a.gpu_slots) valid = 0;   // never dereference a bad slot
-    s_slot[i] = slot;
-    s_valid[i] = valid;
+  } else {
+    n_sel = min(a.n_sel[unit], a.k_blocks);
+    const int n_ld = phase == 1 ? min(a.n_load[unit], a.k_blocks) : 0;
+    const int32_t* ll = a.load_list + (size_t)unit * a.k_blocks * 2;
+    for (int i = tid; i < n_sel; i += kThreads) {
+      const int J = a.sel_idx[(size_t)unit * a.k_blocks + i];
+      int slot = -1, valid = 0;
+      if (J >= 0 && J < a.max_blocks) {
+        slot = a.slot_of_block[(size_t)unit * a.max_blocks + J];
+        valid = min(kBlockTokens, T - J * kBlockTokens);
+      }
+      if (slot < 0 || slot >= a.gpu_slots) valid = 0;   // never dereference a bad slot
+      if (n_ld > 0) {   // phase 1: leave out the blocks still in flight (load list is ascending by block)
+        int lo = 0, hi = n_ld;
+        while (lo < hi) {
+          const int mid = (lo + hi) >> 1;
+          if (ll[2 * mid] < J) lo = mid + 1; else hi = mid;
+        }
+        if (lo < n_ld && ll[2 * lo] == J) valid = 0;
+      }
+      s_slot[i] = slot;
+      s_valid[i] = valid;
+    }
   }
 
   // q slices of this lane for all heads of the group: line v of the row, 16-byte slice c
@@ -222,10 +264,13 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
     for (int i = 0; i < STEPS; ++i)
 #pragma unroll
       for (int v = 0; v < VPL; ++v) kx[i][v].raw = load_stream(kp + i * (kRPW * RP) + v * kLPR);
-    if constexpr (HAS_BIAS) {
+    if (has_bias) {
       const float* bp = a.pool_bias + slot_lin * kBlockTokens + row0;
 #pragma unroll
-      for (int i = 0; i < STEPS; ++i) bx[i] = __builtin_nontemporal_load(bp + i * kRPW);
+      for (int i = 0; i < STEPS; ++i) bx[i] = __builtin_nontemporal_load(bp + i * kRPW) * 1.4426950408889634f;
+    } else {
+#pragma unroll
+      for (int i = 0; i < STEPS; ++i) bx[i] = 0.f;
     }
 #pragma unroll
     for (int i = 0; i < STEPS; ++i)
@@ -235,8 +280,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
     float s[G][STEPS];
 #pragma unroll
     for (int i = 0; i < STEPS; ++i) {
-      float bl = 0.f;
-      if constexpr (HAS_BIAS) bl = bx[i] * 1.4426950408889634f;
+      const float bl = bx[i];
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         float d = kx[i][0].dot(qv[g][0]);
@@ -341,7 +385,24 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
       L = fmaf(s_l[w][g], sc, L);
       O = fmaf(s_acc[w][g][e], sc, O);
     }
-    if (a.splits == 1) {
+    if (phase == 2) {
+      // fold in the partial results of the resident blocks (written by the phase-1 launch)
+      const size_t p0 = ((size_t)unit * a.merge_splits) * G + g;
+      float M2 = M;
+      for (int sp = 0; sp < a.merge_splits; ++sp) M2 = fmaxf(M2, a.part_ml[(p0 + (size_t)sp * G) * 2]);
+      const float sc0 = (M == NEG_INF) ? 0.f : fast_exp2(M - M2);
+      L *= sc0;
+      O *= sc0;
+      for (int sp = 0; sp < a.merge_splits; ++sp) {
+        const size_t pi = p0 + (size_t)sp * G;
+        const float ms = a.part_ml[pi * 2];
+        const float sc = (ms == NEG_INF) ? 0.f : fast_exp2(ms - M2);
+        L = fmaf(a.part_ml[pi * 2 + 1], sc, L);
+        O = fmaf(a.part_o[pi * D + e], sc, O);
+      }
+      M = M2;
+    }
+    if (phase == 2 || (a.splits == 1 && phase == 0)) {
       const size_t o = ((size_t)b * a.n_kv_heads * G + (size_t)h * G + g) * D + e;
       store_out(a.out, o, L > 0.f ? O / L : 0.f, DT);
       if (a.lse && e == 0) a.lse[(size_t)b * a.n_kv_heads * G + h * G + g] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : NEG_INF;
@@ -382,27 +443,17 @@ __global__ __launch_bounds__(kThreads) void decode_combine_kernel(const float* _
   }
 }
 
-template <int DT, int D, int G>
-void launch_partial(const DecodeArgs& a, dim3 grid, hipStream_t s) {
-  if (a.pool_bias)
-    hipLaunchKernelGGL((decode_partial_kernel<DT, D, G, true>), grid, dim3(kThreads), 0, s, a);
-  else
-    hipLaunchKernelGGL((decode_partial_kernel<DT, D, G, false>), grid, dim3(kThreads), 0, s, a);
-}
-
-template <int DT, int D>
+template <int DT, int D, bool OVERLAP>
 bool dispatch_group(int g, const DecodeArgs& a, dim3 grid, hipStream_t s) {
+#define NOSA_CASE(GG)                                                                                       \
+  case GG:                                                                                                  \
+    hipLaunchKernelGGL((decode_partial_kernel<DT, D, GG, OVERLAP>), grid, dim3(kThreads), 0, s, a);         \
+    return true;
   switch (g) {
-    case 1: launch_partial<DT, D, 1>(a, grid, s); return true;
-    case 2: launch_partial<DT, D, 2>(a, grid, s); return true;
-    case 3: launch_partial<DT, D, 3>(a, grid, s); return true;
-    case 4: launch_partial<DT, D, 4>(a, grid, s); return true;
-    case 6: launch_partial<DT, D, 6>(a, grid, s); return true;
-    case 8: launch_partial<DT, D, 8>(a, grid, s); return true;
-    case 12: launch_partial<DT, D, 12>(a, grid, s); return true;
-    case 16: launch_partial<DT, D, 16>(a, grid, s); return true;
+    NOSA_CASE(1) NOSA_CASE(2) NOSA_CASE(3) NOSA_CASE(4) NOSA_CASE(6) NOSA_CASE(8) NOSA_CASE(12) NOSA_CASE(16)
     default: return false;
   }
+#undef NOSA_CASE
 }
 
 }  // namespace
@@ -424,9 +475,28 @@ int decode_default_splits(const nosa_params& p) {
   return s;
 }
 
+namespace {
+
+template <int DT, bool OVERLAP>
+bool dispatch_dim(int D, int G, const DecodeArgs& a, dim3 grid, hipStream_t s) {
+  return D == 128 ? dispatch_group<DT, 128, OVERLAP>(G, a, grid, s) : dispatch_group<DT, 64, OVERLAP>(G, a, grid, s);
+}
+
+template <bool OVERLAP>
+bool dispatch(const nosa_params& p, int G, const DecodeArgs& a, dim3 grid, hipStream_t s) {
+  return p.dtype == NOSA_DTYPE_BF16 ? dispatch_dim<NOSA_DTYPE_BF16, OVERLAP>(p.head_dim, G, a, grid, s)
+                                    : dispatch_dim<NOSA_DTYPE_F32, OVERLAP>(p.head_dim, G, a, grid, s);
+}
+
+}  // namespace
+
+// Attention over the selected blocks.  When `wait_fetch` names an event, the blocks that were
+// already resident are processed first (they do not depend on the gather in flight), then the
+// stream waits for the gather and a second launch processes the fetched blocks and merges both.
 int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v, const float* pool_bias,
                   const int32_t* sel_idx, const int32_t* n_sel, const int32_t* slot_of_block,
-                  const int32_t* n_tokens, void* out, float* lse) {
+                  const int32_t* n_tokens, void* out, float* lse, hipEvent_t wait_fetch,
+                  const int32_t* load_list, const int32_t* n_load) {
   const nosa_params& p = ctx->p;
   const int G = ctx->group, D = p.head_dim, S = ctx->splits;
   DecodeArgs a;
@@ -435,19 +505,35 @@ int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* 
   a.part_o = (float*)ctx->ws;
   a.part_ml = a.part_o ? a.part_o + (size_t)ctx->units * S * G * D : nullptr;
   a.out = out; a.lse = lse;
+  a.load_list = load_list; a.n_load = n_load;
   a.n_kv_heads = p.n_kv_heads; a.gpu_slots = p.gpu_slots; a.k_blocks = p.k_blocks; a.max_blocks = p.max_blocks;
   a.splits = S;
+  a.phase = 0;
+  a.merge_splits = 0;
   a.scale_log2e = ctx->scale * 1.4426950408889634f;
-  const dim3 grid(S, ctx->units);
-  bool ok;
+  if (wait_fetch && load_list && n_load && a.part_o) {
+    a.phase = 1;
+    {
+      TimedLaunch tl(ctx, NOSA_KERNEL_DECODE, ctx->main);
+      NOSA_REQUIRE(ctx, dispatch<true>(p, G, a, dim3(S * ctx->units), ctx->main), NOSA_ESHAPE, "GQA group %d unsupported", G);
+    }
+    NOSA_HIP(ctx, hipGetLastError());
+    NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, wait_fetch, 0));
+    a.phase = 2;
+    a.merge_splits = S;
+    a.splits = 1;
+    {
+      TimedLaunch tl(ctx, NOSA_KERNEL_COMBINE, ctx->main);
+      NOSA_REQUIRE(ctx, dispatch<true>(p, G, a, dim3(ctx->units), ctx->main), NOSA_ESHAPE, "GQA group %d unsupported", G);
+    }
+    NOSA_HIP(ctx, hipGetLastError());
+    return NOSA_OK;
+  }
+  if (wait_fetch) NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, wait_fetch, 0));
   {
     TimedLaunch tl(ctx, NOSA_KERNEL_DECODE, ctx->main);
-    if (p.dtype == NOSA_DTYPE_BF16)
-      ok = D == 128 ? dispatch_group<NOSA_DTYPE_BF16, 128>(G, a, grid, ctx->main) : dispatch_group<NOSA_DTYPE_BF16, 64>(G, a, grid, ctx->main);
-    else
-      ok = D == 128 ? dispatch_group<NOSA_DTYPE_F32, 128>(G, a, grid, ctx->main) : dispatch_group<NOSA_DTYPE_F32, 64>(G, a, grid, ctx->main);
+    NOSA_REQUIRE(ctx, dispatch<false>(p, G, a, dim3(S * ctx->units), ctx->main), NOSA_ESHAPE, "GQA group %d unsupported", G);
   }
-  NOSA_REQUIRE(ctx, ok, NOSA_ESHAPE, "GQA group %d unsupported", G);
   NOSA_HIP(ctx, hipGetLastError());
   if (S > 1) {
     TimedLaunch tl(ctx, NOSA_KERNEL_COMBINE, ctx->main);

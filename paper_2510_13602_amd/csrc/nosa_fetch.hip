@@ -3,14 +3,16 @@
 // pinned host memory (the GPU addresses it over the host link) and write the block's slot in the
 // paged pool.  A block's keys and values are contiguous 8-32 KiB pieces, so every wave-load is a
 // 1 KiB contiguous read; all loads of a piece are issued before the first store so that many
-// requests are in flight on the link.  The list length lives on the device: the grid is sized for
-// the per-step bound (Kq blocks per unit, Theorem 1) and loops when a cold start needs more.
+// requests are in flight on the link.  The list lengths live on the device; nothing is read back.
 #include "nosa_internal.h"
 
 namespace nosa {
 namespace {
 
-constexpr int kThreads = 256;
+#ifndef NOSA_FETCH_THREADS
+#define NOSA_FETCH_THREADS 256
+#endif
+constexpr int kThreads = NOSA_FETCH_THREADS;
 constexpr int kInFlight = 4;   // 16-byte loads per lane before the stores start
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -44,18 +46,26 @@ __device__ __forceinline__ void copy_piece(const u32x4* __restrict__ src, u32x4*
   }
 }
 
-__global__ __launch_bounds__(kThreads) void fetch_kernel(const FetchArgs a) {
-  const int unit = blockIdx.y;
-  const int n = min(a.n_load[unit], a.k_blocks);
-  for (int i = blockIdx.x; i < n; i += gridDim.x) {
-    const int J = a.load_list[((size_t)unit * a.k_blocks + i) * 2];
-    const int s = a.load_list[((size_t)unit * a.k_blocks + i) * 2 + 1];
-    if (J < 0 || J >= a.max_blocks || s < 0 || s >= a.gpu_slots) continue;   // malformed entry: skip, never fault
-    const size_t src = (size_t)unit * a.max_blocks + J;
-    const size_t dst = (size_t)unit * a.gpu_slots + s;
-    copy_piece(a.host_k + src * a.block_vec, a.pool_k + dst * a.block_vec, a.block_vec, threadIdx.x);
-    copy_piece(a.host_v + src * a.block_vec, a.pool_v + dst * a.block_vec, a.block_vec, threadIdx.x);
-    if (a.host_bias) copy_piece(a.host_bias + src * a.bias_vec, a.pool_bias + dst * a.bias_vec, a.bias_vec, threadIdx.x);
+// A persistent grid: workgroup w takes units w, w + gridDim.x, ... and copies each unit's listed
+// blocks in turn, 16 KiB in flight per workgroup.  Measured on MI355X (PCIe Gen5 x16): 16 workgroups
+// reach 36 GB/s, 64 reach 52 GB/s, 512 reach 56 GB/s (read latency under load is several microseconds,
+// so about 1 MiB has to be in flight).  Host reads in flight slow HBM reads of kernels running at
+// the same time (global, not per CU or per XCD): the attention over resident blocks that overlaps the
+// gather runs 1.3x slower at 64 workgroups and ~8x slower at 512 -- but it still ends before the
+// gather does, so the step time is lowest with the widest gather.
+__global__ __launch_bounds__(kThreads) void fetch_kernel(const FetchArgs a, int units) {
+  for (int unit = blockIdx.x; unit < units; unit += gridDim.x) {
+    const int n = min(a.n_load[unit], a.k_blocks);
+    for (int i = 0; i < n; ++i) {
+      const int J = a.load_list[((size_t)unit * a.k_blocks + i) * 2];
+      const int s = a.load_list[((size_t)unit * a.k_blocks + i) * 2 + 1];
+      if (J < 0 || J >= a.max_blocks || s < 0 || s >= a.gpu_slots) continue;   // malformed entry: skip, never fault
+      const size_t src = (size_t)unit * a.max_blocks + J;
+      const size_t dst = (size_t)unit * a.gpu_slots + s;
+      copy_piece(a.host_k + src * a.block_vec, a.pool_k + dst * a.block_vec, a.block_vec, threadIdx.x);
+      copy_piece(a.host_v + src * a.block_vec, a.pool_v + dst * a.block_vec, a.block_vec, threadIdx.x);
+      if (a.host_bias) copy_piece(a.host_bias + src * a.bias_vec, a.pool_bias + dst * a.bias_vec, a.bias_vec, threadIdx.x);
+    }
   }
 }
 
@@ -68,11 +78,9 @@ int launch_fetch(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const vo
   FetchArgs a{(const u32x4*)host_k, (const u32x4*)host_v, (const u32x4*)host_bias, (u32x4*)pool_k, (u32x4*)pool_v,
               (u32x4*)pool_bias, load_list, n_load, p.k_blocks, p.gpu_slots, p.max_blocks,
               p.block_size * p.head_dim * es / 16, p.block_size * 4 / 16};
-  int per_unit = p.kq_blocks > 0 ? p.kq_blocks : 1;
-  if (per_unit > p.k_blocks) per_unit = p.k_blocks;
-  const dim3 grid(per_unit, ctx->units);
+  const int wgs = ctx->fetch_wgs < ctx->units ? ctx->fetch_wgs : ctx->units;
   TimedLaunch tl(ctx, NOSA_KERNEL_FETCH, stream);
-  hipLaunchKernelGGL(fetch_kernel, grid, dim3(kThreads), 0, stream, a);
+  hipLaunchKernelGGL(fetch_kernel, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units);
   NOSA_HIP(ctx, hipGetLastError());
   return NOSA_OK;
 }

@@ -38,8 +38,11 @@ struct nosa_ctx {
   hipEvent_t ev_fetch = nullptr;    // recorded on side after the gather kernel
   bool select_recorded = false;
   bool fetch_pending = false;
+  const int32_t* pending_load_list = nullptr;   // arguments of the fetch in flight (caller-owned, dev)
+  const int32_t* pending_n_load = nullptr;
   int overlap = 1;
   int splits = 1;
+  int fetch_wgs = 512;      // workgroups of the gather kernel (capped by the number of units)
   void* ws = nullptr;
   size_t ws_bytes = 0;
   bool timing = false;
@@ -85,7 +88,8 @@ int launch_fetch(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const vo
                  const int32_t* load_list, const int32_t* n_load);
 int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v,
                   const float* pool_bias, const int32_t* sel_idx, const int32_t* n_sel,
-                  const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse);
+                  const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse,
+                  hipEvent_t wait_fetch, const int32_t* load_list, const int32_t* n_load);
 int launch_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const int32_t* n_tokens,
                        void* k_pooled, float* se_pooled);
 int launch_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float* b_new, void* pool_k, void* pool_v,

@@ -35,7 +35,10 @@ def test_1b_shaped_half_resident():
     print("1b: n_load mean per step", [round(r["n_load_mean"], 2) for r in rec], flush=True)
 
 
-def test_1b_overlap_and_serial_give_identical_bits():
+def test_1b_overlap_and_serial_orders_agree():
+    """Fetch on the side stream with two-phase attention (resident blocks first, fetched blocks after the
+    gather) against everything in call order on one stream: identical selections and miss counts; outputs
+    equal up to the summation order of the merge (within one bf16 rounding step)."""
     w = CONFIGS["1b"].replace(batch=4)
     outs = []
     for overlap in (True, False):
@@ -58,8 +61,12 @@ def test_1b_overlap_and_serial_give_identical_bits():
         torch.cuda.synchronize()
         outs.append(res)
         ctx.close()
+    from helpers import widen
     for (o1, s1, n1), (o2, s2, n2) in zip(*outs):
-        assert o1.tobytes() == o2.tobytes() and (s1 == s2).all() and (n1 == n2).all()
+        assert (s1 == s2).all() and (n1 == n2).all()
+        a, b = widen(o1), widen(o2)
+        assert np.isfinite(a).all() and np.isfinite(b).all()
+        assert (np.abs(a - b) <= 2.0 ** -7 * np.maximum(np.abs(a), np.abs(b)) + 1e-6).all()
 
 
 def test_3b_shaped_reduced_batch():
