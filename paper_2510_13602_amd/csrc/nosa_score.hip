@@ -124,6 +124,73 @@ __global__ __launch_bounds__(kThreads) void block_score_kernel(const ScoreArgs a
   }
 }
 
+
+// Fast path for one pooled key per block (pool_kernel == pool_stride == block size): sub-block j is
+// block j, the block max is the identity.  A workgroup streams 128 pooled keys; every lane issues its
+// 8 non-temporal 16-byte loads before the first dot product.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kFastBlocksPerWg = 128;
+
+template <int DT, int D>
+__global__ __launch_bounds__(kThreads) void block_score_simple_kernel(const ScoreArgs a) {
+  constexpr int EPL = DT == NOSA_DTYPE_BF16 ? 8 : 4;
+  constexpr int ES = DT == NOSA_DTYPE_BF16 ? 2 : 4;
+  constexpr int LPR = D / EPL;
+  constexpr int RPW = kWave / LPR;
+  constexpr int GROUPS = (kThreads / kWave) * RPW;
+  constexpr int ITERS = kFastBlocksPerWg / GROUPS;
+
+  const int unit = blockIdx.y;
+  const int b = unit / a.n_kv_heads, h = unit % a.n_kv_heads;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int r = lane / LPR, c = lane % LPR;
+  const int nsub = min(a.n_tokens[b] / kBlockTokens, a.n_sub_max);   // complete blocks
+  const int J0 = blockIdx.x * kFastBlocksPerWg + wave * RPW + r;     // this lane's row in round 0
+
+  const u32x4* kc = (const u32x4*)((const char*)a.k_pooled + (size_t)unit * a.n_sub_max * D * ES);
+  const float* sec = a.se_pooled + (size_t)unit * a.n_sub_max;
+  u32x4 kv[ITERS];
+  float sev[ITERS];
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int J = J0 + it * GROUPS;
+    kv[it] = u32x4{0u, 0u, 0u, 0u};
+    sev[it] = -INFINITY;
+    if (J < nsub) {
+      kv[it] = __builtin_nontemporal_load(kc + (size_t)J * LPR + c);
+      if (c == 0) sev[it] = __builtin_nontemporal_load(sec + J);
+    }
+  }
+
+  float qs[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) qs[e] = 0.f;
+  {
+    const uint4* qp = (const uint4*)((const char*)a.q + ((size_t)b * a.n_kv_heads + h) * a.group * D * ES);
+    for (int g = 0; g < a.group; ++g) {
+      float f[EPL];
+      widen16<DT>(qp[g * LPR + c], f);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) qs[e] += f[e];
+    }
+  }
+
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int J = J0 + it * GROUPS;
+    float f[EPL];
+    widen16<DT>(make_uint4(kv[it].x, kv[it].y, kv[it].z, kv[it].w), f);
+    float d = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) d = fmaf(f[e], qs[e], d);
+    d = row_sum<LPR>(d);
+    if (c == 0 && J < a.max_blocks) {
+      a.sq_blk[(size_t)unit * a.max_blocks + J] = J < nsub ? d : -INFINITY;
+      a.se_blk[(size_t)unit * a.max_blocks + J] = sev[it];
+    }
+  }
+}
+
 }  // namespace
 
 int launch_block_score(nosa_ctx* ctx, const void* q, const void* k_pooled, const float* se_pooled,
@@ -131,8 +198,20 @@ int launch_block_score(nosa_ctx* ctx, const void* q, const void* k_pooled, const
   const nosa_params& p = ctx->p;
   ScoreArgs a{q, k_pooled, se_pooled, n_tokens, sq_blk, se_blk, p.n_kv_heads, ctx->group,
               p.max_blocks, p.n_sub_max, p.pool_kernel, p.pool_stride};
-  const dim3 grid((p.max_blocks + kBlocksPerWg - 1) / kBlocksPerWg, ctx->units);
   TimedLaunch tl(ctx, NOSA_KERNEL_SCORE, ctx->main);
+  if (p.pool_kernel == p.block_size && p.pool_stride == p.block_size) {
+    const dim3 fgrid((p.max_blocks + kFastBlocksPerWg - 1) / kFastBlocksPerWg, ctx->units);
+    if (p.dtype == NOSA_DTYPE_BF16) {
+      if (p.head_dim == 128) hipLaunchKernelGGL((block_score_simple_kernel<NOSA_DTYPE_BF16, 128>), fgrid, dim3(kThreads), 0, ctx->main, a);
+      else hipLaunchKernelGGL((block_score_simple_kernel<NOSA_DTYPE_BF16, 64>), fgrid, dim3(kThreads), 0, ctx->main, a);
+    } else {
+      if (p.head_dim == 128) hipLaunchKernelGGL((block_score_simple_kernel<NOSA_DTYPE_F32, 128>), fgrid, dim3(kThreads), 0, ctx->main, a);
+      else hipLaunchKernelGGL((block_score_simple_kernel<NOSA_DTYPE_F32, 64>), fgrid, dim3(kThreads), 0, ctx->main, a);
+    }
+    NOSA_HIP(ctx, hipGetLastError());
+    return NOSA_OK;
+  }
+  const dim3 grid((p.max_blocks + kBlocksPerWg - 1) / kBlocksPerWg, ctx->units);
   if (p.dtype == NOSA_DTYPE_BF16) {
     if (p.head_dim == 128) hipLaunchKernelGGL((block_score_kernel<NOSA_DTYPE_BF16, 128>), grid, dim3(kThreads), 0, ctx->main, a);
     else hipLaunchKernelGGL((block_score_kernel<NOSA_DTYPE_BF16, 64>), grid, dim3(kThreads), 0, ctx->main, a);
