@@ -159,6 +159,17 @@ int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const v
 int nosa_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const int32_t* n_tokens,
                      void* k_pooled, float* se_pooled);
 
+/* Upstream of the cache update (Alg. 1 fused_linear_projection; Sec. 4 "Kernel Fusion": the eviction
+ * head is fused with the split of the QKV tensor).  qkv [B, (Hq + 2 Hkv) d] dtype holds, per token,
+ * all query heads, then all key heads, then all value heads.  w1 [d, Hkv] and w2 [Hkv] are the fp32
+ * eviction-head weights (importance-score Eq., Sec. 3.1; tau = softplus, no final exp: ED-DMA).
+ *   mode 0 (table of App. D, one gate per KV head):  b[b,h] = softplus(v_h . w1[:,h]) * w2[h]
+ *   mode 1 (the Eq. as printed, shared by the heads): b[b,h] = sum_m softplus(v_h . w1[:,m]) * w2[m]
+ * Outputs: q_out [B,Hq,d], k_new, v_new [B,Hkv,d] (bit copies, ready for RoPE and nosa_append) and
+ * b_new [B,Hkv] fp32.  All pointers dev.                                                          */
+int nosa_split_qkv_evict(nosa_ctx* ctx, const void* qkv, const float* w1, const float* w2, int mode,
+                         void* q_out, void* k_new, void* v_new, float* b_new);
+
 /* Appends the current token of every unit (Alg. 1: the cache engine is updated before Stage 1).
  * k_new, v_new [B,Hkv,d] dtype, b_new [B,Hkv] fp32, all dev.  Token t = n_tokens[b] goes to block
  * J = t / n_b, row t % n_b of the host pool (written by the GPU over the host link) and, when block J

@@ -257,3 +257,19 @@ def append(p: Params, k_new, v_new, b_new, pool_k, pool_v, pool_bias, host_k, ho
     lib().oracle_append(ctypes.byref(pc), _ptr(k_new), _ptr(v_new), _ptr(b_new), _ptr(pool_k), _ptr(pool_v),
                         _ptr(pool_bias), _ptr(host_k), _ptr(host_v), _ptr(host_bias), _ptr(se_blk), _ptr(n_tokens),
                         _ptr(slot_of_block), _ptr(block_of_slot))
+
+
+def split_qkv_evict(p: Params, qkv: np.ndarray, w1: np.ndarray, w2: np.ndarray, mode: int = 0):
+    """Split of the fused QKV activation and the eviction head b = softplus(v W1) (.) W2 (Sec. 3.1)."""
+    B, Hq, H, d = p.batch, p.n_q_heads, p.n_kv_heads, p.head_dim
+    _check(qkv, (B, (Hq + 2 * H) * d), p.np_dtype, "qkv")
+    _check(w1, (d, H), np.float32, "w1")
+    _check(w2, (H,), np.float32, "w2")
+    q = np.empty((B, Hq, d), p.np_dtype)
+    k = np.empty((B, H, d), p.np_dtype)
+    v = np.empty((B, H, d), p.np_dtype)
+    b = np.empty((B, H), np.float64)
+    pc = p.c()
+    lib().oracle_split_qkv_evict(ctypes.byref(pc), _ptr(qkv), _ptr(w1), _ptr(w2), ctypes.c_int(mode), _ptr(q), _ptr(k),
+                                 _ptr(v), _ptr(b))
+    return q, k, v, b

@@ -21,6 +21,7 @@
  *   oracle_attention     the biased attention output of Sec. 3.1 "Attention Calculation"
  *                        (exp(b_j) exp(q k_j + m_j) normalised), restricted to Gamma(t)
  *   oracle_append        the cache update that precedes Stage 1 in Alg. 1, for a growing context
+ *   oracle_split_qkv_evict  QKV split + eviction head (importance-score Eq.; Sec. 4 "Kernel Fusion")
  *
  * Readings taken where the paper is silent (each is a parameter or a stated rule):
  *   - pooling windows are half open, [j*ls, j*ls+lk): exactly lk terms;
@@ -418,4 +419,39 @@ void oracle_append(const oracle_params *p, const void *k_new, const void *v_new,
   }
   for (int b = 0; b < p->batch; ++b)
     if (n_tokens[b] < p->max_blocks * nb) n_tokens[b] += 1;
+}
+
+/* ---- eviction head on the value of the current token (importance-score Eq., Sec. 3.1; ED-DMA row
+ * of the table in App. D: b_j = tau(v_j W_1) (.) W_2, tau = softplus, no final exp) together with
+ * the split of the fused QKV activation (Alg. 1 fused_linear_projection; Sec. 4 "Kernel Fusion").
+ * qkv [B, (Hq + 2 Hkv) d]: all query heads, then all key heads, then all value heads of a token.
+ * w1 [d, Hkv] (row e, column m), w2 [Hkv], both fp32.
+ *   mode 0 (table, one gate per KV head):  b[b,h] = softplus(v_h . w1[:,h]) * w2[h]
+ *   mode 1 (Eq. as printed, W_1 in R^{d x Hkv}, W_2 in R^{Hkv x 1}, shared by the heads):
+ *                                          b[b,h] = sum_m softplus(v_h . w1[:,m]) * w2[m]
+ * q_out [B,Hq,d], k_new, v_new [B,Hkv,d] are bit copies; b_new [B,Hkv] fp64.                      */
+static double softplus64(double x) { return (x > 0 ? x : 0) + log1p(exp(-fabs(x))); }
+
+void oracle_split_qkv_evict(const oracle_params *p, const void *qkv, const float *w1, const float *w2, int mode,
+                            void *q_out, void *k_new, void *v_new, double *b_new) {
+  const int d = p->head_dim, Hq = p->n_q_heads, Hkv = p->n_kv_heads;
+  const size_t es = p->dtype == 0 ? 4 : 2;
+  const size_t row = (size_t)(Hq + 2 * Hkv) * d;
+  for (int b = 0; b < p->batch; ++b) {
+    const char *src = (const char *)qkv + (size_t)b * row * es;
+    memcpy((char *)q_out + (size_t)b * Hq * d * es, src, (size_t)Hq * d * es);
+    memcpy((char *)k_new + (size_t)b * Hkv * d * es, src + (size_t)Hq * d * es, (size_t)Hkv * d * es);
+    memcpy((char *)v_new + (size_t)b * Hkv * d * es, src + (size_t)(Hq + Hkv) * d * es, (size_t)Hkv * d * es);
+    for (int h = 0; h < Hkv; ++h) {
+      const int64_t vb = (int64_t)b * row + (int64_t)(Hq + Hkv + h) * d;
+      double acc = 0.0;
+      for (int m = 0; m < Hkv; ++m) {
+        if (mode == 0 && m != h) continue;
+        double dot = 0.0;
+        for (int e = 0; e < d; ++e) dot += load_elem(qkv, vb + e, p->dtype) * (double)w1[(int64_t)e * Hkv + m];
+        acc += softplus64(dot) * (double)w2[m];
+      }
+      b_new[(int64_t)b * Hkv + h] = acc;
+    }
+  }
 }

@@ -23,7 +23,7 @@ MAX_SPLITS = 16
 EXPORTS = [
     "nosa_validate_params", "nosa_create", "nosa_destroy", "nosa_workspace_bytes", "nosa_set_workspace",
     "nosa_set_splits", "nosa_get_splits", "nosa_set_overlap", "nosa_last_error", "nosa_block_score",
-    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_append", "nosa_timing_enable",
+    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_timing_enable",
     "nosa_timing_read",
 ]
 
@@ -72,6 +72,7 @@ def load_library() -> ctypes.CDLL:
     lib.nosa_sparse_decode.argtypes = [vp, vp, vp, vp, fp, i32p, i32p, i32p, i32p, vp, fp]
     lib.nosa_pool_blocks.argtypes = [vp, vp, fp, i32p, vp, fp]
     lib.nosa_append.argtypes = [vp] + [vp] * 15
+    lib.nosa_split_qkv_evict.argtypes = [vp, vp, fp, fp, ctypes.c_int, vp, vp, vp, fp]
     lib.nosa_timing_enable.argtypes = [vp, ctypes.c_int]
     lib.nosa_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     for name in EXPORTS:
@@ -265,3 +266,12 @@ class Nosa:
             _dev(n_tokens, torch.int32, (B,), "n_tokens"),
             _dev(slot_of_block, torch.int32, (B, H, p.max_blocks), "slot_of_block"),
             _dev(block_of_slot, torch.int32, (B, H, p.gpu_slots), "block_of_slot")))
+
+    def nosa_split_qkv_evict(self, qkv, w1, w2, mode, q_out, k_new, v_new, b_new) -> None:
+        p, B, H = self.p, self._B, self._H
+        d = p.head_dim
+        self._check(self.lib.nosa_split_qkv_evict(
+            self._ctx, _dev(qkv, self.tdtype, (B, (p.n_q_heads + 2 * H) * d), "qkv"),
+            _dev(w1, torch.float32, (d, H), "w1"), _dev(w2, torch.float32, (H,), "w2"), int(mode),
+            _dev(q_out, self.tdtype, (B, p.n_q_heads, d), "q_out"), _dev(k_new, self.tdtype, (B, H, d), "k_new"),
+            _dev(v_new, self.tdtype, (B, H, d), "v_new"), _dev(b_new, torch.float32, (B, H), "b_new")))

@@ -291,6 +291,14 @@ int nosa_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const i
   return nosa::launch_pool_blocks(ctx, keys, bias, n_tokens, k_pooled, se_pooled);
 }
 
+int nosa_split_qkv_evict(nosa_ctx* ctx, const void* qkv, const float* w1, const float* w2, int mode, void* q_out,
+                         void* k_new, void* v_new, float* b_new) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, qkv && w1 && w2 && q_out && k_new && v_new && b_new, NOSA_EINVAL, "nosa_split_qkv_evict: NULL argument");
+  NOSA_REQUIRE(ctx, mode == 0 || mode == 1, NOSA_EINVAL, "nosa_split_qkv_evict: mode %d not in {0, 1}", mode);
+  return nosa::launch_split_qkv_evict(ctx, qkv, w1, w2, mode, q_out, k_new, v_new, b_new);
+}
+
 int nosa_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float* b_new, void* pool_k, void* pool_v,
                 float* pool_bias, void* host_k, void* host_v, float* host_bias, void* k_pooled, float* se_pooled,
                 const float* se_blk, int32_t* n_tokens, int32_t* slot_of_block, int32_t* block_of_slot) {

@@ -95,6 +95,8 @@ int launch_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const
 int launch_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float* b_new, void* pool_k, void* pool_v,
                   float* pool_bias, void* host_k, void* host_v, float* host_bias, void* k_pooled, float* se_pooled,
                   const float* se_blk, int32_t* n_tokens, int32_t* slot_of_block, int32_t* block_of_slot);
+int launch_split_qkv_evict(nosa_ctx* ctx, const void* qkv, const float* w1, const float* w2, int mode, void* q_out,
+                           void* k_new, void* v_new, float* b_new);
 bool decode_supports_group(int g);
 int decode_default_splits(const nosa_params& p);
 

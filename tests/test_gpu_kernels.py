@@ -278,3 +278,29 @@ def test_pool_blocks_bit_exact(dtype, d, lk, ls, T):
     assert to_np(kc).tobytes() == kc_ref.tobytes()
     assert to_np(se).tobytes() == se_ref.tobytes()
     ctx.close()
+
+
+@pytest.mark.parametrize("dtype,d,Hq,Hkv,mode", [("bf16", 128, 32, 8, 0), ("bf16", 128, 32, 8, 1), ("fp32", 64, 4, 1, 0), ("bf16", 64, 16, 2, 1),
+                                                 ("fp32", 128, 24, 4, 0)])
+def test_split_qkv_evict_parity(dtype, d, Hq, Hkv, mode):
+    """QKV split is a bit copy; the eviction-head bias matches the fp64 oracle to fp32 rounding."""
+    import math
+    B = 5
+    w = small_workload(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, dtype=dtype)
+    g = torch.Generator().manual_seed(d + Hq + mode)
+    qkv = (2.0 * torch.randn((B, (Hq + 2 * Hkv) * d), generator=g)).to(w.torch_dtype)
+    w1 = (torch.randn((d, Hkv), generator=g) / math.sqrt(d)).float()
+    w2 = torch.randn((Hkv,), generator=g).float()
+    q_ref, k_ref, v_ref, b_ref = oracle.split_qkv_evict(oracle_params(w), to_np(qkv), w1.numpy(), w2.numpy(), mode)
+    ctx = nosa.Nosa(gpu_params(w), device=DEV)
+    td = w.torch_dtype
+    q = torch.zeros((B, Hq, d), dtype=td, device=DEV)
+    k = torch.zeros((B, Hkv, d), dtype=td, device=DEV)
+    v = torch.zeros((B, Hkv, d), dtype=td, device=DEV)
+    b = torch.full((B, Hkv), float("nan"), device=DEV)
+    ctx.nosa_split_qkv_evict(qkv.to(DEV), w1.to(DEV), w2.to(DEV), mode, q, k, v, b)
+    torch.cuda.synchronize()
+    assert to_np(q).tobytes() == q_ref.tobytes() and to_np(k).tobytes() == k_ref.tobytes() and to_np(v).tobytes() == v_ref.tobytes()
+    # fp32 dot of d products of size O(1) plus a softplus: 1e-5 absolute covers it with margin
+    assert np.abs(b.cpu().numpy().astype(np.float64) - b_ref).max() <= 1e-5 * max(1.0, np.abs(b_ref).max())
+    ctx.close()
