@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work the oracle baseline is given")
     ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--mode", default="fused", choices=["calls", "fused", "graph"],
+                    help="how a step crosses the C ABI: four calls, the single nosa_decode_step entry, or a HIP graph replay")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run five plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
     return ap.parse_args()
@@ -128,7 +130,9 @@ def main():
                               k_blocks=w.k_blocks, kq_blocks=w.kq_blocks, sink_blocks=w.sink_blocks,
                               window_blocks=w.window_blocks, gpu_slots=w.gpu_slots, max_blocks=w.max_blocks,
                               n_sub_max=w.n_sub_max, dtype=w.dtype)
-    ctx = nosa.Nosa(params, device=dev)
+    stream = torch.cuda.Stream(device=dev)          # a real stream (the NULL stream cannot be captured into a graph)
+    torch.cuda.set_stream(stream)
+    ctx = nosa.Nosa(params, stream=stream, device=dev)
     if args.splits:
         ctx.set_splits(args.splits)
     ctx.set_overlap(not args.no_overlap)
@@ -160,13 +164,28 @@ def main():
     def q_of(l, i):
         return queries[l % LH][0 if args.resident else i]
 
+    q_static = [torch.zeros_like(queries[0][0]) for _ in range(L)] if args.mode == "graph" else None
+
+    def do_step(l, q):
+        if args.mode == "calls":
+            layers[l].step(q)
+        elif args.mode == "fused":
+            layers[l].step_fused(q)
+        else:
+            q_static[l].copy_(q)                    # the query lands in the buffer the graph reads
+            layers[l].replay()
+
     # cold start of every layer (fills the pool through the real path), then W warm-up steps
     for l, lc in enumerate(layers):
         lc.step(q_of(l, 0))
     torch.cuda.synchronize()
     cold_loads = float(sum(lc.n_load.float().mean().item() for lc in layers) / L)
+    if args.mode == "graph":
+        for l, lc in enumerate(layers):
+            lc.capture(q_static[l])
+        torch.cuda.synchronize()
     for i in range(args.warmup):
-        layers[i % L].step(q_of(i % L, 1 + i))
+        do_step(i % L, q_of(i % L, 1 + i))
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
 
@@ -182,7 +201,7 @@ def main():
         t0 = time.perf_counter()
         for _ in range(n_steps):
             j = step_no[0]
-            layers[j % L].step(q_of(j % L, 1 + j))
+            do_step(j % L, q_of(j % L, 1 + j))
             step_no[0] += 1
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
@@ -199,16 +218,20 @@ def main():
     dt, kern = timed_region(args.steps)
     loads = torch.stack([lc.n_load.float() for lc in layers[:min(L, args.steps)]])
     mean_load, max_load = float(loads.mean().item()), float(loads.max().item())
-    if args.resident or args.no_overlap:
+    if args.no_overlap:
         dt_alone, kern_alone = dt, kern
     else:
+        mode = args.mode
+        if mode == "graph":                      # graphs were recorded with the overlap order; replay eagerly here
+            args.mode = "fused"
         ctx.set_overlap(False)
         for _ in range(min(8, args.warmup)):
             j = step_no[0]
-            layers[j % L].step(q_of(j % L, 1 + j))
+            do_step(j % L, q_of(j % L, 1 + j))
             step_no[0] += 1
         dt_alone, kern_alone = timed_region(args.steps)
         ctx.set_overlap(True)
+        args.mode = mode
 
     units = w.units
     dec_us = kern_alone["sparse_decode"]
@@ -233,7 +256,7 @@ def main():
         "config": {"workload": f"{w.name}-shaped", "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "context": w.context, "block_size": w.block_size, "k_blocks": w.k_blocks,
                    "kq_blocks": w.kq_blocks, "sink_blocks": w.sink_blocks, "window_blocks": w.window_blocks,
-                   "gpu_slots": w.gpu_slots, "layers_cycled": L, "host_pools": LH, "splits": ctx.splits,
+                   "gpu_slots": w.gpu_slots, "layers_cycled": L, "host_pools": LH, "splits": ctx.splits, "step_entry": args.mode,
                    "fetch": "resident (no misses)" if args.resident else ("side stream" if not args.no_overlap else "main stream")},
         "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<bf16,128,4,false>" if w.name == "8b" else "decode_partial_kernel",
                      "achieved": achieved, "peak": peak, "unit": "GB/s",

@@ -149,6 +149,45 @@ int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const v
                        const float* pool_bias, const int32_t* sel_idx, const int32_t* n_sel,
                        const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse);
 
+/* One whole decode step of one layer = the four calls above, in the order of Alg. 1, behind one
+ * entry point (one boundary crossing per step instead of four).  Every field has the meaning and
+ * memory kind of the like-named argument above; host_bias / pool_bias may both be NULL, lse may be
+ * NULL.                                                                                           */
+typedef struct {
+  const void* q;
+  const void* k_pooled;
+  const float* se_pooled;
+  const int32_t* n_tokens;
+  float* sq_blk;
+  float* se_blk;
+  int32_t* sel_idx;
+  int32_t* n_sel;
+  int32_t* slot_of_block;
+  int32_t* block_of_slot;
+  int32_t* load_list;
+  int32_t* n_load;
+  const void* host_k;
+  const void* host_v;
+  const float* host_bias;
+  void* pool_k;
+  void* pool_v;
+  float* pool_bias;
+  void* out;
+  float* lse;
+} nosa_step_args;
+int nosa_decode_step(nosa_ctx* ctx, const nosa_step_args* args);
+
+/* The same step recorded once into a HIP graph (Sec. 4 "Kernel Fusion": the paper captures the
+ * launch-bound part of the step in a graph) and replayed with one launch.  All pointers are baked
+ * in: the caller refreshes the contents of q (and of the cache tensors) in place between replays.
+ * The graph holds kernel nodes on two branches (gather | attention over resident blocks) joined
+ * before the attention over fetched blocks; it contains no memset nodes.  Kernel timing is not
+ * recorded for replays.  nosa_graph_launch enqueues on the context's main stream.                 */
+typedef struct nosa_graph nosa_graph;
+int nosa_graph_create(nosa_ctx* ctx, const nosa_step_args* args, nosa_graph** out);
+int nosa_graph_launch(nosa_ctx* ctx, nosa_graph* graph);
+int nosa_graph_destroy(nosa_graph* graph);
+
 /* ---- cache maintenance (Alg. 1 update_compressed_k / update_importance_score) ----------------*/
 
 /* Rebuilds k_pooled and se_pooled from a whole cache: K_c[j] = mean of the keys of sub-block j

@@ -23,7 +23,8 @@ MAX_SPLITS = 16
 EXPORTS = [
     "nosa_validate_params", "nosa_create", "nosa_destroy", "nosa_workspace_bytes", "nosa_set_workspace",
     "nosa_set_splits", "nosa_get_splits", "nosa_set_overlap", "nosa_last_error", "nosa_block_score",
-    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_timing_enable",
+    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_decode_step", "nosa_graph_create", "nosa_graph_launch",
+    "nosa_graph_destroy", "nosa_timing_enable",
     "nosa_timing_read",
 ]
 
@@ -40,6 +41,14 @@ class Params(ctypes.Structure):
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "block_size", "pool_kernel", "pool_stride",
         "k_blocks", "kq_blocks", "sink_blocks", "window_blocks", "gpu_slots", "max_blocks", "n_sub_max",
         "dtype")] + [("softmax_scale", ctypes.c_float)]
+
+
+class StepArgs(ctypes.Structure):
+    """Mirror of ``nosa_step_args`` (include/nosa.h): the tensors of one whole decode step."""
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "q", "k_pooled", "se_pooled", "n_tokens", "sq_blk", "se_blk", "sel_idx", "n_sel", "slot_of_block",
+        "block_of_slot", "load_list", "n_load", "host_k", "host_v", "host_bias", "pool_k", "pool_v", "pool_bias",
+        "out", "lse")]
 
 
 _lib = None
@@ -73,6 +82,10 @@ def load_library() -> ctypes.CDLL:
     lib.nosa_pool_blocks.argtypes = [vp, vp, fp, i32p, vp, fp]
     lib.nosa_append.argtypes = [vp] + [vp] * 15
     lib.nosa_split_qkv_evict.argtypes = [vp, vp, fp, fp, ctypes.c_int, vp, vp, vp, fp]
+    lib.nosa_decode_step.argtypes = [vp, ctypes.POINTER(StepArgs)]
+    lib.nosa_graph_create.argtypes = [vp, ctypes.POINTER(StepArgs), ctypes.POINTER(vp)]
+    lib.nosa_graph_launch.argtypes = [vp, vp]
+    lib.nosa_graph_destroy.argtypes = [vp]
     lib.nosa_timing_enable.argtypes = [vp, ctypes.c_int]
     lib.nosa_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     for name in EXPORTS:
@@ -275,3 +288,41 @@ class Nosa:
             _dev(w1, torch.float32, (d, H), "w1"), _dev(w2, torch.float32, (H,), "w2"), int(mode),
             _dev(q_out, self.tdtype, (B, p.n_q_heads, d), "q_out"), _dev(k_new, self.tdtype, (B, H, d), "k_new"),
             _dev(v_new, self.tdtype, (B, H, d), "v_new"), _dev(b_new, torch.float32, (B, H), "b_new")))
+
+    def step_args(self, q, k_pooled, se_pooled, n_tokens, sq_blk, se_blk, sel_idx, n_sel, slot_of_block, block_of_slot,
+                  load_list, n_load, host_k, host_v, host_bias, pool_k, pool_v, pool_bias, out, lse=None) -> StepArgs:
+        """Checks every tensor once and packs the pointers of one whole step."""
+        p, B, H = self.p, self._B, self._H
+        d, nb = p.head_dim, p.block_size
+        kv_host, kv_pool = (B, H, p.max_blocks, nb, d), (B, H, p.gpu_slots, nb, d)
+        for t, name in ((host_k, "host_k"), (host_v, "host_v"), (host_bias, "host_bias")):
+            if t is not None and not (t.is_cuda or t.is_pinned()):
+                raise ValueError(f"{name} must be pinned host memory (or device memory)")
+        v = lambda x: None if x is None else x.value
+        return StepArgs(
+            v(_dev(q, self.tdtype, (B, p.n_q_heads, d), "q")), v(_dev(k_pooled, self.tdtype, (B, H, p.n_sub_max, d), "k_pooled")),
+            v(_dev(se_pooled, torch.float32, (B, H, p.n_sub_max), "se_pooled")), v(_dev(n_tokens, torch.int32, (B,), "n_tokens")),
+            v(_dev(sq_blk, torch.float32, (B, H, p.max_blocks), "sq_blk")), v(_dev(se_blk, torch.float32, (B, H, p.max_blocks), "se_blk")),
+            v(_dev(sel_idx, torch.int32, (B, H, p.k_blocks), "sel_idx")), v(_dev(n_sel, torch.int32, (B, H), "n_sel")),
+            v(_dev(slot_of_block, torch.int32, (B, H, p.max_blocks), "slot_of_block")),
+            v(_dev(block_of_slot, torch.int32, (B, H, p.gpu_slots), "block_of_slot")),
+            v(_dev(load_list, torch.int32, (B, H, p.k_blocks, 2), "load_list")), v(_dev(n_load, torch.int32, (B, H), "n_load")),
+            v(_raw(host_k, self.tdtype, kv_host, "host_k")), v(_raw(host_v, self.tdtype, kv_host, "host_v")),
+            None if host_bias is None else v(_raw(host_bias, torch.float32, kv_host[:4], "host_bias")),
+            v(_dev(pool_k, self.tdtype, kv_pool, "pool_k")), v(_dev(pool_v, self.tdtype, kv_pool, "pool_v")),
+            v(_dev(pool_bias, torch.float32, kv_pool[:4], "pool_bias")),
+            v(_dev(out, self.tdtype, (B, p.n_q_heads, d), "out")), v(_dev(lse, torch.float32, (B, p.n_q_heads), "lse")))
+
+    def nosa_decode_step(self, args: StepArgs) -> None:
+        self._check(self.lib.nosa_decode_step(self._ctx, ctypes.byref(args)))
+
+    def nosa_graph_create(self, args: StepArgs) -> ctypes.c_void_p:
+        g = ctypes.c_void_p()
+        self._check(self.lib.nosa_graph_create(self._ctx, ctypes.byref(args), ctypes.byref(g)))
+        return g
+
+    def nosa_graph_launch(self, graph: ctypes.c_void_p) -> None:
+        self._check(self.lib.nosa_graph_launch(self._ctx, graph))
+
+    def nosa_graph_destroy(self, graph: ctypes.c_void_p) -> None:
+        self.lib.nosa_graph_destroy(graph)

@@ -284,6 +284,87 @@ int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const v
   return nosa::launch_decode(ctx, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse, wait, ll, nl);
 }
 
+static int run_step(nosa_ctx* ctx, const nosa_step_args* a) {
+  int rc = nosa_block_score(ctx, a->q, a->k_pooled, a->se_pooled, a->n_tokens, a->sq_blk, a->se_blk);
+  if (rc != NOSA_OK) return rc;
+  rc = nosa_select(ctx, a->sq_blk, a->se_blk, a->n_tokens, a->sel_idx, a->n_sel, a->slot_of_block, a->block_of_slot,
+                   a->load_list, a->n_load);
+  if (rc != NOSA_OK) return rc;
+  rc = nosa_fetch(ctx, a->host_k, a->host_v, a->host_bias, a->pool_k, a->pool_v, a->pool_bias, a->load_list, a->n_load);
+  if (rc != NOSA_OK) return rc;
+  return nosa_sparse_decode(ctx, a->q, a->pool_k, a->pool_v, a->pool_bias, a->sel_idx, a->n_sel, a->slot_of_block,
+                            a->n_tokens, a->out, a->lse);
+}
+
+int nosa_decode_step(nosa_ctx* ctx, const nosa_step_args* args) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, args, NOSA_EINVAL, "nosa_decode_step: args is NULL");
+  return run_step(ctx, args);
+}
+
+struct nosa_graph {
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+};
+
+int nosa_graph_create(nosa_ctx* ctx, const nosa_step_args* args, nosa_graph** out) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, args && out, NOSA_EINVAL, "nosa_graph_create: NULL argument");
+  *out = nullptr;
+  NOSA_REQUIRE(ctx, ctx->main != nullptr, NOSA_EINVAL, "nosa_graph_create: the default (NULL) stream cannot be captured");
+  if (ctx->fetch_pending) {   // nothing from before the capture may be waited on inside it
+    NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, ctx->ev_fetch, 0));
+    ctx->fetch_pending = false;
+  }
+  nosa_graph* g = new (std::nothrow) nosa_graph();
+  NOSA_REQUIRE(ctx, g, NOSA_EINVAL, "out of host memory");
+  const bool timing = ctx->timing;
+  ctx->timing = false;
+  hipError_t e = hipStreamBeginCapture(ctx->main, hipStreamCaptureModeRelaxed);
+  if (e != hipSuccess) {
+    ctx->timing = timing;
+    delete g;
+    return set_error(ctx, NOSA_EHIP, "hipStreamBeginCapture failed: %s", hipGetErrorString(e));
+  }
+  const int rc = run_step(ctx, args);
+  e = hipStreamEndCapture(ctx->main, &g->graph);
+  ctx->timing = timing;
+  ctx->fetch_pending = false;
+  if (rc != NOSA_OK || e != hipSuccess) {
+    if (g->graph) (void)hipGraphDestroy(g->graph);
+    delete g;
+    if (rc != NOSA_OK) return rc;
+    return set_error(ctx, NOSA_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+  }
+  e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
+  if (e != hipSuccess) {
+    (void)hipGraphDestroy(g->graph);
+    delete g;
+    return set_error(ctx, NOSA_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+  }
+  *out = g;
+  return NOSA_OK;
+}
+
+int nosa_graph_launch(nosa_ctx* ctx, nosa_graph* graph) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, graph && graph->exec, NOSA_EINVAL, "nosa_graph_launch: no graph");
+  if (ctx->fetch_pending) {
+    NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, ctx->ev_fetch, 0));
+    ctx->fetch_pending = false;
+  }
+  NOSA_HIP(ctx, hipGraphLaunch(graph->exec, ctx->main));
+  return NOSA_OK;
+}
+
+int nosa_graph_destroy(nosa_graph* graph) {
+  if (!graph) return NOSA_OK;
+  if (graph->exec) (void)hipGraphExecDestroy(graph->exec);
+  if (graph->graph) (void)hipGraphDestroy(graph->graph);
+  delete graph;
+  return NOSA_OK;
+}
+
 int nosa_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const int32_t* n_tokens,
                      void* k_pooled, float* se_pooled) {
   NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");

@@ -44,6 +44,8 @@ class LayerCache:
         self.n_load = torch.empty((B, H), dtype=torch.int32, device=dev)
         self.out = torch.empty((B, p.n_q_heads, d), dtype=dt, device=dev)
         self.lse = torch.empty((B, p.n_q_heads), dtype=torch.float32, device=dev)
+        self._packed = None
+        self._graph = None
 
     def rebuild_pooled(self) -> None:
         """Pooled keys and pooled importance of the whole cache (reads the host pool from the GPU)."""
@@ -93,3 +95,31 @@ class LayerCache:
         self.select()
         self.fetch()
         return self.decode(q)
+
+    def _args(self, q: torch.Tensor):
+        return self.nosa.step_args(q, self.k_pooled, self.se_pooled, self.n_tokens, self.sq_blk, self.se_blk, self.sel_idx,
+                                   self.n_sel, self.slot_of_block, self.block_of_slot, self.load_list, self.n_load,
+                                   self.host_k, self.host_v, self.host_bias, self.pool_k, self.pool_v, self.pool_bias,
+                                   self.out, self.lse)
+
+    def step_fused(self, q: torch.Tensor) -> torch.Tensor:
+        """The same step through the single entry point (pointers are packed once per query buffer)."""
+        key = q.data_ptr()
+        if self._packed is None or self._packed[0] != key:
+            self._packed = (key, self._args(q))
+        self.nosa.nosa_decode_step(self._packed[1])
+        return self.out
+
+    def capture(self, q_static: torch.Tensor) -> None:
+        """Records the step into a HIP graph that reads its query from ``q_static`` (refreshed in place)."""
+        self.release_graph()
+        self._graph = self.nosa.nosa_graph_create(self._args(q_static))
+
+    def replay(self) -> torch.Tensor:
+        self.nosa.nosa_graph_launch(self._graph)
+        return self.out
+
+    def release_graph(self) -> None:
+        if self._graph is not None:
+            self.nosa.nosa_graph_destroy(self._graph)
+            self._graph = None

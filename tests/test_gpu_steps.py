@@ -98,3 +98,68 @@ def test_growing_context_small_ragged_fp32():
     from pipeline import run_growing
     w = CONFIGS["tiny"].replace(context=64 * 20 + 50, generated=150, pool_kernel=32, pool_stride=16, batch=2)
     run_growing(w, seed=3, steps=150)
+
+
+def _two_layers(w, seed, stream=None):
+    import paper_2510_13602_amd as nosa
+    from helpers import gpu_params
+    from nosa_inputs import make_layer
+    from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+    layer = make_layer(w, seed, 0)
+    ctx = nosa.Nosa(gpu_params(w), stream=stream)
+    hk, hv, hb = pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"])
+    n_tok = torch.full((w.batch,), w.context, dtype=torch.int32)
+    a, b = LayerCache(ctx, hk, hv, hb, n_tok), LayerCache(ctx, hk, hv, hb, n_tok)
+    a.rebuild_pooled()
+    b.rebuild_pooled()
+    return ctx, a, b
+
+
+def test_single_entry_step_equals_four_calls():
+    from helpers import to_np
+    from nosa_inputs import QueryStream
+    w = CONFIGS["1b"].replace(batch=4)
+    ctx, a, b = _two_layers(w, 7)
+    qs = QueryStream(w, 7, 0)
+    for t in range(6):
+        q = qs.next(t).to("cuda:0")
+        oa = a.step(q)
+        ob = b.step_fused(q)
+        torch.cuda.synchronize()
+        assert to_np(oa).tobytes() == to_np(ob).tobytes()
+        assert (a.sel_idx == b.sel_idx).all() and (a.n_load == b.n_load).all() and (a.slot_of_block == b.slot_of_block).all()
+    ctx.close()
+
+
+def test_graph_replays_match_eager_steps():
+    """The step recorded into a HIP graph, replayed 8 times with the program's own eager work and
+    synchronisations between the replays; every replay must equal the eager step on twin state."""
+    from helpers import to_np
+    from nosa_inputs import QueryStream
+    w = CONFIGS["1b"].replace(batch=4)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        ctx, a, b = _two_layers(w, 9, stream=s)
+        qs = QueryStream(w, 9, 0)
+        q_static = torch.zeros((w.batch, w.n_q_heads, w.head_dim), dtype=w.torch_dtype, device="cuda:0")
+        s.synchronize()
+        b.capture(q_static)
+        s.synchronize()
+        # the capture itself launches nothing: state is still the initial one
+        assert (b.slot_of_block == -1).all()
+        scratch = torch.randn(1 << 20, device="cuda:0")
+        for t in range(8):
+            q = qs.next(t).to("cuda:0")
+            q_static.copy_(q)
+            oa = a.step(q)
+            ob = b.replay()
+            s.synchronize()
+            assert (a.sel_idx == b.sel_idx).all(), f"replay {t}: selections differ"
+            assert (a.n_load == b.n_load).all() and (a.load_list == b.load_list).all()
+            assert (a.slot_of_block == b.slot_of_block).all() and (a.block_of_slot == b.block_of_slot).all()
+            assert to_np(oa).tobytes() == to_np(ob).tobytes(), f"replay {t}: outputs differ"
+            assert to_np(a.pool_k).tobytes() == to_np(b.pool_k).tobytes()
+            scratch = (scratch * 1.0001 + 1.0).sort().values          # unrelated eager work between replays
+            float(scratch.sum().item())
+        b.release_graph()
+        ctx.close()
