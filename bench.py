@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work the oracle baseline is given")
     ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--kq", type=int, default=0, help="override the query-aware budget Kq (blocks); Ke shrinks accordingly")
+    ap.add_argument("--study", default="", choices=["", "transfer"],
+                    help="transfer: block-wise versus element-wise host-to-device gather over miss fractions (prints one JSON line per point)")
     ap.add_argument("--mode", default="fused", choices=["calls", "fused", "graph"],
                     help="how a step crosses the C ABI: four calls, the single nosa_decode_step entry, or a HIP graph replay")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -98,6 +101,71 @@ def cpu_baseline(w, host, queries, sample_batch, seconds):
                       f"fp64, OpenMP over units, {dt:.1f} s"}
 
 
+def transfer_study(args):
+    """Block-wise versus element-wise host-to-device gather (Sec. 3.2 "Comparison with DMA"; Sec. 4
+    "Offloading Communication") at the paper's micro-benchmark shape: batch 64, 2 KV heads, d 128, a budget of
+    4096 tokens (64 blocks of 64) per head, of which a fraction 1 - gamma is fetched from pinned host memory."""
+    import numpy as np
+    import torch
+    import paper_2510_13602_amd as nosa
+    from nosa_inputs import Workload
+    dev = "cuda:0"
+    w = Workload("transfer", 64, 2, 2, 128, 16384, 64, 16, 1, 16, 64, "bf16", 1, 1, "key_offset")
+    params = nosa.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                              k_blocks=w.k_blocks, kq_blocks=w.kq_blocks, sink_blocks=w.sink_blocks,
+                              window_blocks=w.window_blocks, gpu_slots=w.gpu_slots, max_blocks=w.max_blocks,
+                              n_sub_max=w.n_sub_max, dtype=w.dtype)
+    ctx = nosa.Nosa(params, device=dev)
+    ctx.set_overlap(False)
+    B, H, N, C, nb, d = w.batch, w.n_kv_heads, w.max_blocks, w.gpu_slots, w.block_size, w.head_dim
+    g = torch.Generator(device=dev).manual_seed(args.seed)
+    host = []
+    for shape, dt in (((B, H, N, nb, d), torch.bfloat16), ((B, H, N, nb, d), torch.bfloat16), ((B, H, N, nb), torch.float32)):
+        t = torch.empty(shape, dtype=dt, pin_memory=True)
+        t.copy_(torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(dt))
+        host.append(t)
+    pool_k = torch.zeros((B, H, C, nb, d), dtype=torch.bfloat16, device=dev)
+    pool_v = torch.zeros_like(pool_k)
+    pool_b = torch.zeros((B, H, C, nb), dtype=torch.float32, device=dev)
+    rng = np.random.default_rng(args.seed)
+    reps = 20
+    for gamma in (0.5, 0.6, 0.7, 0.75, 0.8, 0.9, 0.95):
+        n_blk = round((1 - gamma) * C)
+        n_tok = n_blk * nb
+        # block-wise: n_blk random blocks into random slots; element-wise: n_tok random tokens into random rows
+        ll = np.full((B, H, w.k_blocks, 2), -1, np.int32)
+        tl = np.full((B, H, n_tok, 2), -1, np.int32)
+        for b in range(B):
+            for h in range(H):
+                ll[b, h, :n_blk, 0] = np.sort(rng.choice(N, n_blk, replace=False))
+                ll[b, h, :n_blk, 1] = rng.choice(C, n_blk, replace=False)
+                tl[b, h, :, 0] = rng.choice(N * nb, n_tok, replace=False)
+                tl[b, h, :, 1] = rng.choice(C * nb, n_tok, replace=False)
+        ll_d, tl_d = torch.from_numpy(ll).to(dev), torch.from_numpy(tl).to(dev)
+        nl_d = torch.full((B, H), n_blk, dtype=torch.int32, device=dev)
+        nt_d = torch.full((B, H), n_tok, dtype=torch.int32, device=dev)
+        nbytes = B * H * n_tok * (2 * d * 2 + 4)
+        for pattern in ("block", "element"):
+            def go():
+                if pattern == "block":
+                    ctx.nosa_fetch(host[0], host[1], host[2], pool_k, pool_v, pool_b, ll_d, nl_d)
+                else:
+                    ctx.nosa_fetch_tokens(host[0], host[1], host[2], pool_k, pool_v, pool_b, tl_d, nt_d)
+            go()
+            torch.cuda.synchronize()
+            ctx.timing_enable(True)
+            ctx.timing_read(nosa.KERNEL_FETCH)
+            for _ in range(reps):
+                go()
+            torch.cuda.synchronize()
+            ms, n = ctx.timing_read(nosa.KERNEL_FETCH)
+            ctx.timing_enable(False)
+            print(json.dumps({"study": "transfer", "pattern": pattern, "gamma": gamma, "fetched_per_head": n_blk if pattern == "block" else n_tok,
+                              "unit": "blocks" if pattern == "block" else "tokens", "bytes": nbytes, "avg_us": 1e3 * ms / n,
+                              "host_link_GBps": nbytes / (ms / n * 1e-3) / 1e9}), flush=True)
+    ctx.close()
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -121,7 +189,11 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "copies": 5}))
         return
+    if args.study == "transfer":
+        return transfer_study(args)
     w = CONFIGS[args.workload]
+    if args.kq:
+        w = w.replace(kq_blocks=args.kq)
     L = args.layers or min(w.layers, 32)
     LH = max(1, min(args.host_layers, L))
     t_setup = time.perf_counter()

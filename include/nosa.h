@@ -140,6 +140,14 @@ int nosa_fetch(nosa_ctx* ctx, const void* host_k, const void* host_v, const floa
                void* pool_k, void* pool_v, float* pool_bias, const int32_t* load_list,
                const int32_t* n_load);
 
+/* Element-wise counterpart of nosa_fetch, for the block-wise versus element-wise comparison of
+ * Sec. 3.2 ("Comparison with DMA"): copies single token rows.  token_list [B,Hkv,max_list,2] dev holds
+ * (token index in the host cache, row index in the unit's pool viewed as C*n_b rows); n_list [B,Hkv] dev.
+ * Runs on the main stream (a study entry point, not part of the decode step).                     */
+int nosa_fetch_tokens(nosa_ctx* ctx, const void* host_k, const void* host_v, const float* host_bias,
+                      void* pool_k, void* pool_v, float* pool_bias, const int32_t* token_list,
+                      const int32_t* n_list, int32_t max_list);
+
 /* Stage 2, attention (output Eq. of Sec. 3.1 "Attention Calculation"): for every query head,
  * softmax over the tokens j < T of the selected blocks of  softmax_scale * q.k_j + b_j, times V;
  * exp(b_j) exp(q k_j + m_j) of the paper is the same thing with the mask m_j realised by visiting

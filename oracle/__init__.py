@@ -273,3 +273,14 @@ def split_qkv_evict(p: Params, qkv: np.ndarray, w1: np.ndarray, w2: np.ndarray, 
     lib().oracle_split_qkv_evict(ctypes.byref(pc), _ptr(qkv), _ptr(w1), _ptr(w2), ctypes.c_int(mode), _ptr(q), _ptr(k),
                                  _ptr(v), _ptr(b))
     return q, k, v, b
+
+
+def fetch_tokens(p: Params, host_k, host_v, host_bias, pool_k, pool_v, pool_bias, token_list, n_list) -> None:
+    """Element-wise (token-granular) host-to-pool copies; in place on the pool arrays."""
+    B, H = p.batch, p.n_kv_heads
+    M = token_list.shape[2]
+    _check(token_list, (B, H, M, 2), np.int32, "token_list")
+    _check(n_list, (B, H), np.int32, "n_list")
+    pc = p.c()
+    lib().oracle_fetch_tokens(ctypes.byref(pc), _ptr(host_k), _ptr(host_v), _ptr(host_bias), _ptr(pool_k), _ptr(pool_v),
+                              _ptr(pool_bias), _ptr(token_list), _ptr(n_list), ctypes.c_int(M))

@@ -455,3 +455,22 @@ void oracle_split_qkv_evict(const oracle_params *p, const void *qkv, const float
     }
   }
 }
+
+/* ---- element-wise transfer (Sec. 3.2 "Comparison with DMA": token-granular host-to-device copies,
+ * the pattern that block-wise selection avoids).  token_list [B,Hkv,M,2] = (token index in the host
+ * cache, row index in the GPU pool viewed as [C*nb] rows), n_list [B,Hkv].  Copies K row, V row, bias. */
+void oracle_fetch_tokens(const oracle_params *p, const void *host_k, const void *host_v, const float *host_bias,
+                         void *pool_k, void *pool_v, float *pool_bias, const int32_t *token_list, const int32_t *n_list,
+                         int max_list) {
+  const int nb = p->block_size, d = p->head_dim, C = p->gpu_slots;
+  const size_t rowb = (size_t)d * (p->dtype == 0 ? 4 : 2);
+  const int units = p->batch * p->n_kv_heads;
+  for (int u = 0; u < units; ++u)
+    for (int i = 0; i < n_list[u]; ++i) {
+      const int t = token_list[((int64_t)u * max_list + i) * 2], r = token_list[((int64_t)u * max_list + i) * 2 + 1];
+      const size_t src = (size_t)u * p->max_blocks * nb + t, dst = (size_t)u * C * nb + r;
+      memcpy((char *)pool_k + dst * rowb, (const char *)host_k + src * rowb, rowb);
+      memcpy((char *)pool_v + dst * rowb, (const char *)host_v + src * rowb, rowb);
+      if (host_bias && pool_bias) pool_bias[dst] = host_bias[src];
+    }
+}

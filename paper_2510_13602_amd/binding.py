@@ -23,7 +23,7 @@ MAX_SPLITS = 16
 EXPORTS = [
     "nosa_validate_params", "nosa_create", "nosa_destroy", "nosa_workspace_bytes", "nosa_set_workspace",
     "nosa_set_splits", "nosa_get_splits", "nosa_set_overlap", "nosa_last_error", "nosa_block_score",
-    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_decode_step", "nosa_graph_create", "nosa_graph_launch",
+    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_fetch_tokens", "nosa_decode_step", "nosa_graph_create", "nosa_graph_launch",
     "nosa_graph_destroy", "nosa_timing_enable",
     "nosa_timing_read",
 ]
@@ -82,6 +82,7 @@ def load_library() -> ctypes.CDLL:
     lib.nosa_pool_blocks.argtypes = [vp, vp, fp, i32p, vp, fp]
     lib.nosa_append.argtypes = [vp] + [vp] * 15
     lib.nosa_split_qkv_evict.argtypes = [vp, vp, fp, fp, ctypes.c_int, vp, vp, vp, fp]
+    lib.nosa_fetch_tokens.argtypes = [vp, vp, vp, fp, vp, vp, fp, i32p, i32p, ctypes.c_int32]
     lib.nosa_decode_step.argtypes = [vp, ctypes.POINTER(StepArgs)]
     lib.nosa_graph_create.argtypes = [vp, ctypes.POINTER(StepArgs), ctypes.POINTER(vp)]
     lib.nosa_graph_launch.argtypes = [vp, vp]
@@ -326,3 +327,18 @@ class Nosa:
 
     def nosa_graph_destroy(self, graph: ctypes.c_void_p) -> None:
         self.lib.nosa_graph_destroy(graph)
+
+    def nosa_fetch_tokens(self, host_k, host_v, host_bias, pool_k, pool_v, pool_bias, token_list, n_list) -> None:
+        p, B, H = self.p, self._B, self._H
+        kv_host = (B, H, p.max_blocks, p.block_size, p.head_dim)
+        kv_pool = (B, H, p.gpu_slots, p.block_size, p.head_dim)
+        M = token_list.shape[2]
+        for t, name in ((host_k, "host_k"), (host_v, "host_v"), (host_bias, "host_bias")):
+            if t is not None and not (t.is_cuda or t.is_pinned()):
+                raise ValueError(f"{name} must be pinned host memory (or device memory)")
+        self._check(self.lib.nosa_fetch_tokens(
+            self._ctx, _raw(host_k, self.tdtype, kv_host, "host_k"), _raw(host_v, self.tdtype, kv_host, "host_v"),
+            None if host_bias is None else _raw(host_bias, torch.float32, kv_host[:4], "host_bias"),
+            _dev(pool_k, self.tdtype, kv_pool, "pool_k"), _dev(pool_v, self.tdtype, kv_pool, "pool_v"),
+            _dev(pool_bias, torch.float32, kv_pool[:4], "pool_bias"),
+            _dev(token_list, torch.int32, (B, H, M, 2), "token_list"), _dev(n_list, torch.int32, (B, H), "n_list"), M))

@@ -264,6 +264,17 @@ int nosa_fetch(nosa_ctx* ctx, const void* host_k, const void* host_v, const floa
   return NOSA_OK;
 }
 
+int nosa_fetch_tokens(nosa_ctx* ctx, const void* host_k, const void* host_v, const float* host_bias, void* pool_k,
+                      void* pool_v, float* pool_bias, const int32_t* token_list, const int32_t* n_list, int32_t max_list) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, host_k && host_v && pool_k && pool_v && token_list && n_list && max_list >= 0, NOSA_EINVAL,
+               "nosa_fetch_tokens: bad argument");
+  NOSA_REQUIRE(ctx, (host_bias == nullptr) == (pool_bias == nullptr), NOSA_EINVAL,
+               "nosa_fetch_tokens: host_bias and pool_bias must both be given or both be NULL");
+  return nosa::launch_fetch_tokens(ctx, ctx->main, host_k, host_v, host_bias, pool_k, pool_v, pool_bias, token_list, n_list,
+                                   max_list);
+}
+
 int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v,
                        const float* pool_bias, const int32_t* sel_idx, const int32_t* n_sel,
                        const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse) {

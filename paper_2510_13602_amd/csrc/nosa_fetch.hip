@@ -69,6 +69,60 @@ __global__ __launch_bounds__(kThreads) void fetch_kernel(const FetchArgs a, int 
   }
 }
 
+// Element-wise counterpart (Sec. 3.2 "Comparison with DMA"): single token rows instead of blocks.
+// A row of K (or V) is d*es bytes = 8..32 lanes of 16 bytes; a workgroup copies 256*16/row_bytes rows
+// per pass, several passes in flight.  Same persistent grid as the block-wise gather.
+struct TokenFetchArgs {
+  const u32x4* host_k;
+  const u32x4* host_v;
+  const float* host_bias;
+  u32x4* pool_k;
+  u32x4* pool_v;
+  float* pool_bias;
+  const int32_t* token_list;   // [units][max_list][2] (host token, pool row)
+  const int32_t* n_list;
+  int max_list, gpu_rows, host_rows;
+  int row_vec;                 // 16-byte vectors per row
+};
+
+__global__ __launch_bounds__(kThreads) void fetch_tokens_kernel(const TokenFetchArgs a, int units) {
+  const int lpr = a.row_vec;                       // lanes per row
+  const int rows_per_pass = kThreads / lpr;
+  const int rr = threadIdx.x / lpr, cc = threadIdx.x % lpr;
+  for (int unit = blockIdx.x; unit < units; unit += gridDim.x) {
+    const int n = min(a.n_list[unit], a.max_list);
+    const int32_t* tl = a.token_list + (size_t)unit * a.max_list * 2;
+    for (int base = 0; base < n; base += rows_per_pass * kInFlight) {
+      u32x4 kb[kInFlight], vb[kInFlight];
+      float bb[kInFlight];
+      int dst[kInFlight];
+#pragma unroll
+      for (int i = 0; i < kInFlight; ++i) {
+        const int e = base + i * rows_per_pass + rr;
+        dst[i] = -1;
+        if (e < n) {
+          const int t = tl[2 * e], r = tl[2 * e + 1];
+          if (t >= 0 && t < a.host_rows && r >= 0 && r < a.gpu_rows) {
+            dst[i] = r;
+            const size_t src = ((size_t)unit * a.host_rows + t);
+            kb[i] = __builtin_nontemporal_load(a.host_k + src * lpr + cc);
+            vb[i] = __builtin_nontemporal_load(a.host_v + src * lpr + cc);
+            if (a.host_bias && cc == 0) bb[i] = __builtin_nontemporal_load(a.host_bias + src);
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < kInFlight; ++i) {
+        if (dst[i] < 0) continue;
+        const size_t d = ((size_t)unit * a.gpu_rows + dst[i]);
+        a.pool_k[d * lpr + cc] = kb[i];
+        a.pool_v[d * lpr + cc] = vb[i];
+        if (a.host_bias && cc == 0) a.pool_bias[d] = bb[i];
+      }
+    }
+  }
+}
+
 }  // namespace
 
 int launch_fetch(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const void* host_v, const float* host_bias,
@@ -85,4 +139,21 @@ int launch_fetch(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const vo
   return NOSA_OK;
 }
 
+}  // namespace nosa
+
+namespace nosa {
+int launch_fetch_tokens(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const void* host_v, const float* host_bias,
+                        void* pool_k, void* pool_v, float* pool_bias, const int32_t* token_list, const int32_t* n_list,
+                        int max_list) {
+  const nosa_params& p = ctx->p;
+  const int es = p.dtype == NOSA_DTYPE_F32 ? 4 : 2;
+  TokenFetchArgs a{(const u32x4*)host_k, (const u32x4*)host_v, host_bias, (u32x4*)pool_k, (u32x4*)pool_v, pool_bias,
+                   token_list, n_list, max_list, p.gpu_slots * p.block_size, p.max_blocks * p.block_size,
+                   p.head_dim * es / 16};
+  const int wgs = ctx->fetch_wgs < ctx->units ? ctx->fetch_wgs : ctx->units;
+  TimedLaunch tl(ctx, NOSA_KERNEL_FETCH, stream);
+  hipLaunchKernelGGL(fetch_tokens_kernel, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units);
+  NOSA_HIP(ctx, hipGetLastError());
+  return NOSA_OK;
+}
 }  // namespace nosa

@@ -97,6 +97,9 @@ int launch_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const flo
                   const float* se_blk, int32_t* n_tokens, int32_t* slot_of_block, int32_t* block_of_slot);
 int launch_split_qkv_evict(nosa_ctx* ctx, const void* qkv, const float* w1, const float* w2, int mode, void* q_out,
                            void* k_new, void* v_new, float* b_new);
+int launch_fetch_tokens(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const void* host_v, const float* host_bias,
+                        void* pool_k, void* pool_v, float* pool_bias, const int32_t* token_list, const int32_t* n_list,
+                        int max_list);
 bool decode_supports_group(int g);
 int decode_default_splits(const nosa_params& p);
 

@@ -304,3 +304,35 @@ def test_split_qkv_evict_parity(dtype, d, Hq, Hkv, mode):
     # fp32 dot of d products of size O(1) plus a softplus: 1e-5 absolute covers it with margin
     assert np.abs(b.cpu().numpy().astype(np.float64) - b_ref).max() <= 1e-5 * max(1.0, np.abs(b_ref).max())
     ctx.close()
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 64), ("bf16", 64), ("fp32", 128)])
+def test_fetch_tokens_element_wise(dtype, d):
+    """Token-granular gather (the element-wise pattern of Sec. 3.2): listed rows only, byte exact."""
+    w = small_workload(batch=2, n_q_heads=2, n_kv_heads=2, head_dim=d, context=64 * 30, k_blocks=8, kq_blocks=2,
+                       gpu_slots=8, dtype=dtype)
+    rng = np.random.default_rng(d + 1)
+    layer = make_layer(w, 37, 0)
+    from paper_2510_13602_amd.runtime import pinned_like
+    hk, hv, hb = pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"])
+    B, H, C, M = w.batch, w.n_kv_heads, w.gpu_slots, 300
+    tl = np.full((B, H, M, 2), -1, np.int32)
+    nl = np.zeros((B, H), np.int32)
+    for b in range(B):
+        for h in range(H):
+            n = [0, 1, 300, 77][b * H + h]
+            tl[b, h, :n, 0] = rng.choice(64 * 30, size=n, replace=False)
+            tl[b, h, :n, 1] = rng.choice(C * 64, size=n, replace=False)
+            nl[b, h] = n
+    td = w.torch_dtype
+    pk0 = torch.randn((B, H, C, 64, d), device=DEV).to(td)
+    pv0 = torch.randn((B, H, C, 64, d), device=DEV).to(td)
+    pb0 = torch.randn((B, H, C, 64), device=DEV)
+    ref_k, ref_v, ref_b = to_np(pk0), to_np(pv0), to_np(pb0)
+    oracle.fetch_tokens(oracle_params(w), to_np(hk), to_np(hv), to_np(hb), ref_k, ref_v, ref_b, tl, nl)
+    ctx = nosa.Nosa(gpu_params(w), device=DEV)
+    pk, pv, pb = pk0.clone(), pv0.clone(), pb0.clone()
+    ctx.nosa_fetch_tokens(hk, hv, hb, pk, pv, pb, torch.from_numpy(tl).to(DEV), torch.from_numpy(nl).to(DEV))
+    torch.cuda.synchronize()
+    assert to_np(pk).tobytes() == ref_k.tobytes() and to_np(pv).tobytes() == ref_v.tobytes() and to_np(pb).tobytes() == ref_b.tobytes()
+    ctx.close()
