@@ -69,6 +69,9 @@ typedef struct {
   int32_t max_blocks;                             /* capacity of the per-unit block tables          */
   int32_t n_sub_max;                              /* capacity of k_pooled / se_pooled per unit      */
   int32_t dtype;                                  /* NOSA_DTYPE_F32 or NOSA_DTYPE_BF16 (q, K, V, out) */
+  int32_t victim_policy;                          /* which free slots a miss overwrites: 0 ascending slot
+                                                     order; 1 empty slots, then the least important block
+                                                     (smallest se_blk) first -- matters only when C > K      */
   float softmax_scale;                            /* multiplies q.k only; <= 0 selects 1/sqrt(d)     */
 } nosa_params;
 
@@ -124,8 +127,9 @@ int nosa_block_score(nosa_ctx* ctx, const void* q, const void* k_pooled, const f
  * block index.  sel_idx receives Gamma(t) in ascending order.
  * Load positions (Sec. 4 "Memory Layout and Block Selection"; Alg. 1 generate_load_positions):
  * the selected blocks without a slot, in ascending order, are paired with the slots (ascending)
- * that are empty or hold a block outside Gamma(t); both residency maps are updated in place and
- * the pairs are written to load_list / n_load.  With C == K and an unchanged cache, n_load <= Kq
+ * that are empty or hold a block outside Gamma(t) (with victim_policy 1: of those slots, the empty
+ * ones and then the ones whose block has the smallest se_blk are used, handed out in ascending slot
+ * order); both residency maps are updated in place and the pairs are written to load_list / n_load.  With C == K and an unchanged cache, n_load <= Kq
  * on every step after the first (Theorem 1).  All pointers dev; nothing is read back.            */
 int nosa_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const int32_t* n_tokens,
                 int32_t* sel_idx, int32_t* n_sel, int32_t* slot_of_block, int32_t* block_of_slot,

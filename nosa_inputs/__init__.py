@@ -70,6 +70,7 @@ class Workload:
     pool_kernel: int = 64
     pool_stride: int = 64
     generated: int = 0           # tokens appended during the run (growing context)
+    victim_policy: int = 0       # residency policy passed through to both sides (no arithmetic here)
 
     @property
     def group(self) -> int:

@@ -35,7 +35,7 @@ class _Params(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "block_size", "pool_kernel", "pool_stride",
         "k_blocks", "kq_blocks", "sink_blocks", "window_blocks", "gpu_slots", "max_blocks",
-        "n_sub_max", "dtype")] + [("softmax_scale", ctypes.c_double)]
+        "n_sub_max", "dtype", "victim_policy")] + [("softmax_scale", ctypes.c_double)]
 
 
 @dataclass
@@ -56,12 +56,13 @@ class Params:
     block_size: int = 64
     pool_kernel: int = 64
     pool_stride: int = 64
+    victim_policy: int = 0
 
     def c(self) -> _Params:
         return _Params(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.block_size,
                        self.pool_kernel, self.pool_stride, self.k_blocks, self.kq_blocks,
                        self.sink_blocks, self.window_blocks, self.gpu_slots, self.max_blocks,
-                       self.n_sub_max, self.dtype, float(self.softmax_scale))
+                       self.n_sub_max, self.dtype, self.victim_policy, float(self.softmax_scale))
 
     @property
     def units(self) -> int:
@@ -155,8 +156,21 @@ def select(p: Params, sq_blk: np.ndarray, se_blk: np.ndarray, n_tokens: np.ndarr
     return (sel, n_sel, kind) if with_kind else (sel, n_sel)
 
 
-def load(p: Params, sel_idx: np.ndarray, n_sel: np.ndarray, slot_of_block: np.ndarray, block_of_slot: np.ndarray):
-    """Set difference of the selection against the resident map; updates both maps in place."""
+def load(p: Params, sel_idx: np.ndarray, n_sel: np.ndarray, slot_of_block: np.ndarray, block_of_slot: np.ndarray,
+         se_blk: Optional[np.ndarray] = None, n_tokens: Optional[np.ndarray] = None):
+    """Set difference of the selection against the resident map; updates both maps in place.
+    With ``p.victim_policy == 1`` the block-level importance ``se_blk`` ranks the victims."""
+    if p.victim_policy == 1:
+        B, H = p.batch, p.n_kv_heads
+        se_blk = np.ascontiguousarray(se_blk, dtype=np.float64)
+        _check(se_blk, (B, H, p.max_blocks), np.float64, "se_blk")
+        _check(n_tokens, (B,), np.int32, "n_tokens")
+        load_list = np.empty((B, H, p.k_blocks, 2), dtype=np.int32)
+        n_load = np.empty((B, H), dtype=np.int32)
+        pc = p.c()
+        lib().oracle_load_policy(ctypes.byref(pc), _ptr(sel_idx), _ptr(n_sel), _ptr(se_blk), _ptr(n_tokens),
+                                 _ptr(slot_of_block), _ptr(block_of_slot), _ptr(load_list), _ptr(n_load))
+        return load_list, n_load
     B, H = p.batch, p.n_kv_heads
     _check(sel_idx, (B, H, p.k_blocks), np.int32, "sel_idx")
     _check(n_sel, (B, H), np.int32, "n_sel")
@@ -230,7 +244,7 @@ def params_from_workload(w, **over) -> Params:
               window_blocks=w.window_blocks, gpu_slots=w.gpu_slots, max_blocks=w.max_blocks,
               n_sub_max=w.n_sub_max, dtype=0 if w.dtype == "fp32" else 1,
               softmax_scale=1.0 / float(w.head_dim) ** 0.5, block_size=w.block_size,
-              pool_kernel=w.pool_kernel, pool_stride=w.pool_stride)
+              pool_kernel=w.pool_kernel, pool_stride=w.pool_stride, victim_policy=getattr(w, "victim_policy", 0))
     kw.update(over)
     return Params(**kw)
 

@@ -60,6 +60,7 @@ typedef struct {
   int32_t max_blocks;   /* Nmax: blocks per unit in the host pool and in the maps */
   int32_t n_sub_max;    /* sub-blocks per unit in k_pooled / se_pooled            */
   int32_t dtype;        /* 0 fp32, 1 bf16                                         */
+  int32_t victim_policy; /* 0: free slots in ascending order; 1: least important block first */
   double softmax_scale;
 } oracle_params;
 
@@ -251,6 +252,65 @@ void oracle_select(const oracle_params *p, const double *sq_blk, const double *s
 /* ---- load positions: Gamma(t) against the resident map -----------------------------------
  * in/out slot_of_block [B,Hkv,Nmax], block_of_slot [B,Hkv,C]; out load_list [B,Hkv,K,2]
  * (block, slot) pairs, -1 padded; n_load [B,Hkv].                                           */
+/* victim_policy 1 (a GPU pool larger than the selection, C > K): among the free slots the ones
+ * used are the empty ones (or ones holding a block beyond the current context) first, then those
+ * whose block has the smallest block-level importance
+ * se_blk (ties: lower slot); the chosen slots are then handed out in ascending slot order.        */
+typedef struct { int cls; double se; int slot; } victim_key;
+static int victim_cmp(const void *a, const void *b) {
+  const victim_key *x = (const victim_key *)a, *y = (const victim_key *)b;
+  if (x->cls != y->cls) return x->cls - y->cls;
+  if (x->se != y->se) return x->se < y->se ? -1 : 1;
+  return x->slot - y->slot;
+}
+static int int_cmp(const void *a, const void *b) { return *(const int *)a - *(const int *)b; }
+
+void oracle_load_policy(const oracle_params *p, const int32_t *sel_idx, const int32_t *n_sel, const double *se_blk,
+                        const int32_t *n_tokens, int32_t *slot_of_block, int32_t *block_of_slot, int32_t *load_list,
+                        int32_t *n_load) {
+  const int K = p->k_blocks, C = p->gpu_slots;
+  const int units = p->batch * p->n_kv_heads;
+  for (int u = 0; u < units; ++u) {
+    const int N = (n_tokens[u / p->n_kv_heads] + p->block_size - 1) / p->block_size;   /* blocks in use */
+    const int32_t *sel = sel_idx + (int64_t)u * K;
+    int32_t *sob = slot_of_block + (int64_t)u * p->max_blocks;
+    int32_t *bos = block_of_slot + (int64_t)u * C;
+    int32_t *ll = load_list + (int64_t)u * K * 2;
+    uint8_t *in_gamma = (uint8_t *)calloc((size_t)p->max_blocks, 1);
+    for (int i = 0; i < n_sel[u]; ++i) in_gamma[sel[i]] = 1;
+    int n_miss = 0;
+    for (int i = 0; i < n_sel[u]; ++i) if (sob[sel[i]] < 0) ++n_miss;
+    victim_key *fr = (victim_key *)malloc(sizeof(victim_key) * (size_t)C);
+    int nf = 0;
+    for (int s = 0; s < C; ++s) {
+      if (bos[s] >= 0 && in_gamma[bos[s]]) continue;
+      const int stale = bos[s] < 0 || bos[s] >= N;     /* empty, or a block beyond the current context */
+      fr[nf].cls = stale ? 0 : 1;
+      fr[nf].se = stale ? 0.0 : se_blk[(int64_t)u * p->max_blocks + bos[s]];
+      fr[nf].slot = s;
+      ++nf;
+    }
+    if (p->victim_policy == 1) qsort(fr, (size_t)nf, sizeof(victim_key), victim_cmp);
+    const int take = n_miss < nf ? n_miss : nf;
+    int *chosen = (int *)malloc(sizeof(int) * (size_t)(take > 0 ? take : 1));
+    for (int i = 0; i < take; ++i) chosen[i] = fr[i].slot;
+    qsort(chosen, (size_t)take, sizeof(int), int_cmp);
+    int nl = 0;
+    for (int i = 0; i < n_sel[u] && nl < take; ++i) {
+      const int J = sel[i];
+      if (sob[J] >= 0) continue;
+      const int s = chosen[nl];
+      if (bos[s] >= 0) sob[bos[s]] = -1;
+      bos[s] = J; sob[J] = s;
+      ll[2 * nl] = J; ll[2 * nl + 1] = s;
+      ++nl;
+    }
+    n_load[u] = nl;
+    for (int i = nl; i < K; ++i) { ll[2 * i] = -1; ll[2 * i + 1] = -1; }
+    free(in_gamma); free(fr); free(chosen);
+  }
+}
+
 void oracle_load(const oracle_params *p, const int32_t *sel_idx, const int32_t *n_sel,
                  int32_t *slot_of_block, int32_t *block_of_slot, int32_t *load_list, int32_t *n_load) {
   const int K = p->k_blocks, C = p->gpu_slots;

@@ -40,7 +40,7 @@ class Params(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "block_size", "pool_kernel", "pool_stride",
         "k_blocks", "kq_blocks", "sink_blocks", "window_blocks", "gpu_slots", "max_blocks", "n_sub_max",
-        "dtype")] + [("softmax_scale", ctypes.c_float)]
+        "dtype", "victim_policy")] + [("softmax_scale", ctypes.c_float)]
 
 
 class StepArgs(ctypes.Structure):
@@ -98,13 +98,13 @@ def load_library() -> ctypes.CDLL:
 
 def make_params(*, batch, n_q_heads, n_kv_heads, head_dim, k_blocks, kq_blocks, sink_blocks, window_blocks,
                 gpu_slots, max_blocks, n_sub_max, dtype, softmax_scale=0.0, block_size=64, pool_kernel=64,
-                pool_stride=64) -> Params:
+                pool_stride=64, victim_policy=0) -> Params:
     if isinstance(dtype, torch.dtype):
         dtype = {torch.float32: DTYPE_F32, torch.bfloat16: DTYPE_BF16}[dtype]
     elif isinstance(dtype, str):
         dtype = {"fp32": DTYPE_F32, "bf16": DTYPE_BF16}[dtype]
     return Params(batch, n_q_heads, n_kv_heads, head_dim, block_size, pool_kernel, pool_stride, k_blocks,
-                  kq_blocks, sink_blocks, window_blocks, gpu_slots, max_blocks, n_sub_max, dtype,
+                  kq_blocks, sink_blocks, window_blocks, gpu_slots, max_blocks, n_sub_max, dtype, victim_policy,
                   float(softmax_scale))
 
 

@@ -63,6 +63,7 @@ static int validate(const nosa_params* p, char* msg, size_t len) {
   if (p->n_q_heads % p->n_kv_heads != 0)
     return fail(NOSA_EINVAL, "n_q_heads (%d) must be a multiple of n_kv_heads (%d)", p->n_q_heads, p->n_kv_heads);
   if (p->dtype != NOSA_DTYPE_F32 && p->dtype != NOSA_DTYPE_BF16) return fail(NOSA_EINVAL, "unknown dtype %d", p->dtype);
+  if (p->victim_policy != 0 && p->victim_policy != 1) return fail(NOSA_EINVAL, "unknown victim_policy %d", p->victim_policy);
   if (p->head_dim != 64 && p->head_dim != 128) return fail(NOSA_ESHAPE, "head_dim %d not in {64, 128}", p->head_dim);
   if (p->block_size != nosa::kBlockTokens) return fail(NOSA_ESHAPE, "block_size %d unsupported (64 only)", p->block_size);
   if (!nosa::decode_supports_group(p->n_q_heads / p->n_kv_heads))
@@ -77,6 +78,8 @@ static int validate(const nosa_params* p, char* msg, size_t len) {
                 p->window_blocks, p->kq_blocks, p->k_blocks);
   if (p->k_blocks > nosa::kMaxSelBlocks) return fail(NOSA_ESHAPE, "k_blocks %d > %d", p->k_blocks, nosa::kMaxSelBlocks);
   if (p->gpu_slots < p->k_blocks) return fail(NOSA_ESHAPE, "gpu_slots (%d) < k_blocks (%d)", p->gpu_slots, p->k_blocks);
+  if (p->victim_policy == 1 && p->gpu_slots > nosa::kMaxSelectBlocks)
+    return fail(NOSA_ESHAPE, "victim_policy 1 supports at most %d gpu_slots", nosa::kMaxSelectBlocks);
   if (p->max_blocks < 1 || p->max_blocks > nosa::kMaxSelectBlocks)
     return fail(NOSA_ESHAPE, "max_blocks %d not in [1, %d]", p->max_blocks, nosa::kMaxSelectBlocks);
   if (p->n_sub_max < 0) return fail(NOSA_EINVAL, "n_sub_max < 0");

@@ -78,7 +78,7 @@ struct SelectArgs {
   int32_t* block_of_slot;
   int32_t* load_list;
   int32_t* n_load;
-  int n_kv_heads, max_blocks, k_blocks, kq_blocks, sink_blocks, window_blocks, gpu_slots;
+  int n_kv_heads, max_blocks, k_blocks, kq_blocks, sink_blocks, window_blocks, gpu_slots, victim_policy;
 };
 
 // R = ceil(max_blocks / 64): candidate keys per lane, register resident.
@@ -88,6 +88,7 @@ __global__ __launch_bounds__(kWave) void select_kernel(const SelectArgs a) {
   int32_t* miss = (int32_t*)smem;                       // [K]
   int32_t* victim = miss + a.k_blocks;                  // [K]
   uint8_t* flags = (uint8_t*)(victim + a.k_blocks);     // [R*64] 0 none, 1 forced, 2 query-aware, 3 query-agnostic
+  uint8_t* vflags = flags + R * kWave;                  // [R*64] victim_policy 1: slots chosen as victims
 
   const int unit = blockIdx.x;
   const int b = unit / a.n_kv_heads;
@@ -141,6 +142,29 @@ __global__ __launch_bounds__(kWave) void select_kernel(const SelectArgs a) {
   n_sel = min(n_sel, K);
   for (int i = n_sel + lane; i < K; i += kWave) sel[i] = -1;
 
+  // victim_policy 1: of the free slots keep the n_miss "cheapest": empty ones, then the ones whose
+  // block has the smallest importance (largest inverted key), ties to the lower slot
+  const bool ranked = a.victim_policy == 1 && n_miss > 0;
+  if (ranked) {
+    uint32_t vkey[R];
+    int n_free = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int s = r * kWave + lane;
+      uint32_t key = 0u;
+      if (s < a.gpu_slots) {
+        const int blk = bos[s];
+        if (blk < 0 || blk >= N) key = 0xffffffffu;
+        else if (flags[blk] == 0) key = ~order_key(se[blk]);
+      }
+      vkey[r] = key;
+      vflags[s] = 0;
+      n_free += (int)__popcll(__ballot(key != 0u));
+    }
+    take_top<R, false>(vkey, vkey, vflags, min(n_miss, n_free), n_free, 1, lane);
+    __syncthreads();
+  }
+
   // victims: slots (ascending) that are empty or hold a block outside Gamma(t); the first n_miss are used
   int n_vict = 0;
   for (int base = 0; base < a.gpu_slots && n_vict < n_miss; base += kWave) {
@@ -148,7 +172,7 @@ __global__ __launch_bounds__(kWave) void select_kernel(const SelectArgs a) {
     bool free_slot = false;
     if (s < a.gpu_slots) {
       const int blk = bos[s];
-      free_slot = blk < 0 || blk >= N || flags[blk] == 0;
+      free_slot = ranked ? vflags[s] != 0 : (blk < 0 || blk >= N || flags[blk] == 0);
     }
     const uint64_t m = __ballot(free_slot);
     const int pos = n_vict + lanes_below(m, lane);
@@ -185,11 +209,13 @@ int launch_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const
                   int32_t* load_list, int32_t* n_load) {
   const nosa_params& p = ctx->p;
   SelectArgs a{sq_blk, se_blk, n_tokens, sel_idx, n_sel, slot_of_block, block_of_slot, load_list, n_load,
-               p.n_kv_heads, p.max_blocks, p.k_blocks, p.kq_blocks, p.sink_blocks, p.window_blocks, p.gpu_slots};
-  const int regs = (p.max_blocks + kWave - 1) / kWave;
+               p.n_kv_heads, p.max_blocks, p.k_blocks, p.kq_blocks, p.sink_blocks, p.window_blocks, p.gpu_slots,
+               p.victim_policy};
+  int regs = (p.max_blocks + kWave - 1) / kWave;
+  if (p.victim_policy == 1 && (p.gpu_slots + kWave - 1) / kWave > regs) regs = (p.gpu_slots + kWave - 1) / kWave;
   const int R = regs <= 8 ? 8 : regs <= 16 ? 16 : regs <= 32 ? 32 : 64;
   NOSA_REQUIRE(ctx, regs <= 64, NOSA_ESHAPE, "selection supports at most %d blocks per unit", kMaxSelectBlocks);
-  const size_t smem = (size_t)p.k_blocks * 8 + (size_t)R * kWave;
+  const size_t smem = (size_t)p.k_blocks * 8 + 2 * (size_t)R * kWave;
   const dim3 grid(ctx->units), block(kWave);
   TimedLaunch tl(ctx, NOSA_KERNEL_SELECT, ctx->main);
   switch (R) {

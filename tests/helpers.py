@@ -38,7 +38,8 @@ def gpu_params(w: Workload, **over):
               k_blocks=w.k_blocks, kq_blocks=w.kq_blocks, sink_blocks=w.sink_blocks,
               window_blocks=w.window_blocks, gpu_slots=w.gpu_slots, max_blocks=w.max_blocks,
               n_sub_max=w.n_sub_max, dtype=w.dtype, softmax_scale=1.0 / math.sqrt(w.head_dim),
-              block_size=w.block_size, pool_kernel=w.pool_kernel, pool_stride=w.pool_stride)
+              block_size=w.block_size, pool_kernel=w.pool_kernel, pool_stride=w.pool_stride,
+              victim_policy=w.victim_policy)
     kw.update(over)
     return nosa.make_params(**kw)
 

@@ -36,7 +36,7 @@ class OracleLayer:
     def step(self, q: np.ndarray, attention: bool = True):
         sq, se = self.scores(q)
         sel, n_sel = oracle.select(self.p, sq, se, self.n_tok)
-        ll, n_load = oracle.load(self.p, sel, n_sel, self.sob, self.bos)
+        ll, n_load = oracle.load(self.p, sel, n_sel, self.sob, self.bos, se, self.n_tok)
         oracle.fetch(self.p, self.hk, self.hv, self.hb, self.pk, self.pv, self.pb, ll, n_load)
         out = lse = None
         if attention:

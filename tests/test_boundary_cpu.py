@@ -34,7 +34,7 @@ def _good(**kw):
 
 
 def test_params_struct_matches_header_layout():
-    assert ctypes.sizeof(nosa.Params) == 16 * 4
+    assert ctypes.sizeof(nosa.Params) == 17 * 4
     nosa.validate_params(_good())
     assert nosa.load_library().nosa_workspace_bytes(_good()) >= 4 * 2 * 16 * 4 * 130 * 4
 
@@ -48,6 +48,7 @@ def test_params_struct_matches_header_layout():
     (dict(gpu_slots=32), nosa.binding.NOSA_ESHAPE),          # C < K
     (dict(window_blocks=0), nosa.binding.NOSA_EINVAL),
     (dict(dtype=7), nosa.binding.NOSA_EINVAL),
+    (dict(victim_policy=2), nosa.binding.NOSA_EINVAL),
     (dict(k_blocks=512, gpu_slots=512), nosa.binding.NOSA_ESHAPE),
     (dict(max_blocks=100000), nosa.binding.NOSA_ESHAPE),
     (dict(n_sub_max=513), nosa.binding.NOSA_EINVAL),

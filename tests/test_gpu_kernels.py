@@ -161,7 +161,7 @@ def _select_case(w, sq, se, n_tok, sob0, bos0):
     po = oracle_params(w)
     sel_ref, nsel_ref = oracle.select(po, sq.astype(np.float64), se.astype(np.float64), n_tok)
     sob_ref, bos_ref = sob0.copy(), bos0.copy()
-    ll_ref, nload_ref = oracle.load(po, sel_ref, nsel_ref, sob_ref, bos_ref)
+    ll_ref, nload_ref = oracle.load(po, sel_ref, nsel_ref, sob_ref, bos_ref, se.astype(np.float64), n_tok)
     ctx = nosa.Nosa(gpu_params(w), device=DEV)
     B, H, K = w.batch, w.n_kv_heads, w.k_blocks
     sel = torch.full((B, H, K), -7, dtype=torch.int32, device=DEV)
@@ -182,6 +182,7 @@ def _select_case(w, sq, se, n_tok, sob0, bos0):
 
 
 @pytest.mark.parametrize("N,K,Kq,Ns,Nw,C,ties", [
+    (128, 32, 8, 1, 8, 64, "policy1"), (300, 40, 8, 1, 16, 200, "policy1-ties"), (64, 16, 4, 1, 4, 16, "policy1"),
     (512, 64, 8, 1, 16, 64, False), (512, 64, 8, 1, 16, 64, True), (128, 32, 8, 1, 8, 64, False),
     (32, 8, 2, 1, 1, 8, True), (300, 64, 16, 1, 16, 80, True), (1000, 128, 32, 2, 20, 128, False),
     (40, 64, 8, 1, 16, 64, False), (4096, 256, 64, 4, 32, 256, True), (70, 64, 0, 1, 16, 64, True),
@@ -190,9 +191,11 @@ def _select_case(w, sq, se, n_tok, sob0, bos0):
 def test_select_and_load_positions_bit_exact(N, K, Kq, Ns, Nw, C, ties):
     rng = np.random.default_rng(N * 7 + K)
     T = 64 * N - 13
+    policy = 1 if isinstance(ties, str) else 0
+    ties = ties is True or ties == "policy1-ties"
     w = small_workload(batch=4, n_q_heads=2, n_kv_heads=2, context=T, k_blocks=K, kq_blocks=Kq, sink_blocks=Ns,
-                       window_blocks=Nw, gpu_slots=C)
-    print(f"case N{N} K{K} Kq{Kq} Ns{Ns} Nw{Nw} C{C} ties={ties}", flush=True)
+                       window_blocks=Nw, gpu_slots=C, victim_policy=policy)
+    print(f"case N{N} K{K} Kq{Kq} Ns{Ns} Nw{Nw} C{C} ties={ties} policy={policy}", flush=True)
     shape = (w.batch, w.n_kv_heads, w.max_blocks)
     if ties:
         sq = rng.integers(-3, 4, shape).astype(np.float32)

@@ -141,3 +141,35 @@ def test_planted_blocks_are_picked_query_aware_on_tiny():
         _, n_load = oracle.load(p, sel, n_sel, sob, bos)
         if t > 0:
             assert n_load[0, 0] <= 2
+
+
+def test_importance_ranked_victims_against_brute_force():
+    """victim_policy 1 (C > K): the slots overwritten are the empty ones first, then the free slots whose
+    block has the smallest block-level importance; the misses themselves are the same set difference."""
+    rng = np.random.default_rng(77)
+    K, Kq, Ns, Nw, C, N = 16, 4, 1, 3, 40, 90
+    T = 64 * N
+    w = small_workload(batch=3, context=T, k_blocks=K, kq_blocks=Kq, sink_blocks=Ns, window_blocks=Nw, gpu_slots=C,
+                       victim_policy=1)
+    p = oracle_params(w)
+    n_tok = np.full((w.batch,), T, np.int32)
+    se = rng.standard_normal((w.batch, w.n_kv_heads, N))
+    sob = np.full((w.batch, w.n_kv_heads, N), -1, np.int32)
+    bos = np.full((w.batch, w.n_kv_heads, C), -1, np.int32)
+    for t in range(10):
+        sq = rng.standard_normal((w.batch, w.n_kv_heads, N)) * 3
+        sel, n_sel = oracle.select(p, sq, se, n_tok)
+        before_sob, before_bos = sob.copy(), bos.copy()
+        ll, n_load = oracle.load(p, sel, n_sel, sob, bos, se, n_tok)
+        _check_maps(p, sob, bos, sel, n_sel)
+        for b in range(w.batch):
+            for h in range(w.n_kv_heads):
+                gamma = set(sel[b, h, :n_sel[b, h]].tolist())
+                resident = set(np.nonzero(before_sob[b, h] >= 0)[0].tolist())
+                miss = sorted(gamma - resident)
+                assert ll[b, h, :n_load[b, h], 0].tolist() == miss
+                free = [s for s in range(C) if before_bos[b, h, s] < 0 or before_bos[b, h, s] not in gamma]
+                rank = sorted(free, key=lambda s: (0, 0.0, s) if before_bos[b, h, s] < 0
+                              else (1, se[b, h, before_bos[b, h, s]], s))
+                want = sorted(rank[:len(miss)])
+                assert ll[b, h, :n_load[b, h], 1].tolist() == want
