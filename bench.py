@@ -26,7 +26,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=32)
-    ap.add_argument("--workload", default="8b", choices=["tiny", "1b", "3b", "8b"])
+    ap.add_argument("--workload", default="8b", choices=["tiny", "1b", "3b", "8b", "longgen"])
     ap.add_argument("--layers", type=int, default=0, help="distinct GPU layer states to cycle (0 = workload default, max 32)")
     ap.add_argument("--host-layers", type=int, default=2, help="distinct pinned host pools (each 8 GiB at the 8B shape)")
     ap.add_argument("--splits", type=int, default=0, help="override the number of attention splits")
@@ -166,6 +166,92 @@ def transfer_study(args):
     ctx.close()
 
 
+def longgen_bench(args):
+    """Long-generation 8B-shaped workload: prompt 4096, then one token per step is produced upstream
+    (QKV split + eviction head), appended (host pool, GPU slot, pooled arrays) and attended.  A step is
+    split_qkv_evict -> append -> score -> select -> fetch -> attention of one layer; two layer states cycle."""
+    import torch
+    import paper_2510_13602_amd as nosa
+    from nosa_inputs import CONFIGS, QueryStream, append_token, make_layer
+    from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+    dev = "cuda:0"
+    total = args.warmup + args.steps
+    w = CONFIGS["longgen"].replace(generated=total + 1)
+    L = args.layers or 2
+    stream = torch.cuda.Stream(device=dev)
+    torch.cuda.set_stream(stream)
+    params = nosa.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                              k_blocks=w.k_blocks, kq_blocks=w.kq_blocks, sink_blocks=w.sink_blocks,
+                              window_blocks=w.window_blocks, gpu_slots=w.gpu_slots, max_blocks=w.max_blocks,
+                              n_sub_max=w.n_sub_max, dtype=w.dtype)
+    ctx = nosa.Nosa(params, stream=stream, device=dev)
+    layers, streams = [], []
+    for l in range(L):
+        lay = make_layer(w, args.seed, l, device=dev)
+        lc = LayerCache(ctx, pinned_like(lay["host_k"]), pinned_like(lay["host_v"]), pinned_like(lay["host_bias"]),
+                        torch.full((w.batch,), w.context, dtype=torch.int32))
+        lc.rebuild_pooled()
+        layers.append(lc)
+        streams.append(QueryStream(w, args.seed, l, device=dev))
+        del lay
+    B, Hq, H, d = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
+    g = torch.Generator(device=dev).manual_seed(args.seed + 5)
+    w1 = (torch.randn((d, H), generator=g, device=dev) / d ** 0.5).float()
+    w2 = torch.randn((H,), generator=g, device=dev).float()
+    # fused activations of every step: drifting queries | appended keys | appended values
+    n_rounds = (total + L - 1) // L + 1
+    qkv = [[None] * n_rounds for _ in range(L)]
+    for l in range(L):
+        for t in range(n_rounds):
+            tok = append_token(w, args.seed, l, t + 1, device=dev)
+            qkv[l][t] = torch.cat([streams[l].next(t).reshape(B, Hq * d), tok["k_new"].reshape(B, H * d),
+                                   tok["v_new"].reshape(B, H * d)], dim=1).contiguous()
+    td = w.torch_dtype
+    q_out = [torch.empty((B, Hq, d), dtype=td, device=dev) for _ in range(L)]
+    k_new = torch.empty((B, H, d), dtype=td, device=dev)
+    v_new = torch.empty((B, H, d), dtype=td, device=dev)
+    b_new = torch.empty((B, H), dtype=torch.float32, device=dev)
+    for l, lc in enumerate(layers):                     # step 0: the prompt's last token is already cached
+        lc.step_fused(qkv[l][0][:, :Hq * d].reshape(B, Hq, d).contiguous())
+    torch.cuda.synchronize()
+
+    def do_step(i):
+        l, t = i % L, i // L + 1
+        ctx.nosa_split_qkv_evict(qkv[l][t], w1, w2, 0, q_out[l], k_new, v_new, b_new)
+        layers[l].append(k_new, v_new, b_new)
+        layers[l].step_fused(q_out[l])
+
+    for i in range(args.warmup):
+        do_step(i)
+    torch.cuda.synchronize()
+    ctx.timing_enable(True)
+    for k in range(7):
+        ctx.timing_read(k)
+    t0 = time.perf_counter()
+    for i in range(args.warmup, total):
+        do_step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.timing_enable(False)
+    kern = {}
+    for k, name in enumerate(nosa.KERNEL_NAMES):
+        ms, n = ctx.timing_read(k)
+        kern[name] = (1e3 * ms / n) if n else None
+    loads = torch.stack([lc.n_load.float() for lc in layers])
+    line = {
+        "metric": "sparse decode steps/sec (batch x KV heads x layer units), growing context", "value": w.units * args.steps / dt,
+        "unit": "unit-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "long-generation 8b-shaped", "batch": B, "n_q_heads": Hq, "n_kv_heads": H, "head_dim": d,
+                   "prompt": w.context, "tokens_at_end": int(layers[0].n_tokens[0].item()), "k_blocks": w.k_blocks,
+                   "kq_blocks": w.kq_blocks, "layers_cycled": L, "upstream": "split_qkv_evict + append every step"},
+        "kernels_avg_us": kern,
+        "fetch": {"mean_blocks_per_unit": float(loads.mean().item()), "max_blocks_per_unit": float(loads.max().item())},
+    }
+    ctx.close()
+    print(json.dumps(line), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -191,6 +277,8 @@ def main():
         return
     if args.study == "transfer":
         return transfer_study(args)
+    if args.workload == "longgen":
+        return longgen_bench(args)
     w = CONFIGS[args.workload]
     if args.kq:
         w = w.replace(kq_blocks=args.kq)
@@ -230,11 +318,13 @@ def main():
     # queries: one stream per host pool (the planted directions belong to the pool)
     streams = [QueryStream(w, args.seed, hl, device=dev) for hl in range(LH)]
     total = args.warmup + args.steps
-    n_q = 1 if args.resident else 2 * total + L + 16
+    n_q = 1 if args.resident else (2 * total + 16) // L + 4
     queries = [[streams[hl].next(t) for t in range(n_q)] for hl in range(LH)]
 
     def q_of(l, i):
-        return queries[l % LH][0 if args.resident else i]
+        # a layer's own query stream advances by one per visit of that layer (keeps the step-to-step
+        # correlation of the AR(1) workloads); i counts steps over all layers
+        return queries[l % LH][0 if args.resident else (i + L - 1) // L]
 
     q_static = [torch.zeros_like(queries[0][0]) for _ in range(L)] if args.mode == "graph" else None
 

@@ -244,8 +244,10 @@ int nosa_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float
 #define NOSA_KERNEL_SELECT 1
 #define NOSA_KERNEL_FETCH 2
 #define NOSA_KERNEL_DECODE 3  /* the split attention kernel (dominant) */
-#define NOSA_KERNEL_COMBINE 4
-#define NOSA_KERNEL_COUNT 5
+#define NOSA_KERNEL_COMBINE 4 /* merge of split results, or the second (fetched blocks + merge) launch */
+#define NOSA_KERNEL_EVICT 5   /* nosa_split_qkv_evict                                           */
+#define NOSA_KERNEL_APPEND 6  /* the launches of nosa_append together                           */
+#define NOSA_KERNEL_COUNT 7
 /* When enabled, each launch of the kernels above is bracketed by HIP events on the stream it runs
  * on.  nosa_timing_read synchronises those events, returns the summed duration and the number of
  * launches since the last read, and resets the counters.  At most 4096 launches per kernel are

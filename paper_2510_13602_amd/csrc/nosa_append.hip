@@ -153,6 +153,7 @@ int launch_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const flo
   AppendArgs a{k_new, v_new, b_new, pool_k, pool_v, pool_bias, host_k, host_v, host_bias, k_pooled, se_pooled, se_blk,
                n_tokens, slot_of_block, block_of_slot, p.batch, p.n_kv_heads, p.head_dim, p.max_blocks, p.n_sub_max,
                p.gpu_slots, p.sink_blocks, p.window_blocks, p.pool_kernel, p.pool_stride, p.dtype};
+  TimedLaunch tl(ctx, NOSA_KERNEL_APPEND, ctx->main);
   hipLaunchKernelGGL(append_kernel, dim3(ctx->units), dim3(kWave), 0, ctx->main, a);
   NOSA_HIP(ctx, hipGetLastError());
   if (p.n_sub_max > 0) {

@@ -85,6 +85,7 @@ int launch_split_qkv_evict(nosa_ctx* ctx, const void* qkv, const float* w1, cons
   NOSA_REQUIRE(ctx, mode == 0 || p.n_kv_heads <= 16, NOSA_ESHAPE, "eviction head mode 1 supports at most 16 KV heads");
   EvictArgs a{qkv, w1, w2, q_out, k_new, v_new, b_new, p.n_q_heads, p.n_kv_heads, p.head_dim, p.dtype, mode};
   const int rows = p.n_q_heads + 2 * p.n_kv_heads;
+  TimedLaunch tl(ctx, NOSA_KERNEL_EVICT, ctx->main);
   hipLaunchKernelGGL(split_qkv_evict_kernel, dim3(p.batch * rows), dim3(kWave), 0, ctx->main, a);
   NOSA_HIP(ctx, hipGetLastError());
   return NOSA_OK;
