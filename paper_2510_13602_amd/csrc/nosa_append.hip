@@ -3,6 +3,7 @@
 // sub-blocks the token completes, advance n_tokens.  Three small launches, none on the timed path.
 #include <cmath>
 
+#include "nosa_device.h"
 #include "nosa_internal.h"
 
 namespace nosa {
@@ -27,11 +28,8 @@ struct AppendArgs {
   int batch, n_kv_heads, head_dim, max_blocks, n_sub_max, gpu_slots, sink_blocks, window_blocks, pool_kernel, pool_stride, dtype;
 };
 
-__device__ __forceinline__ uint32_t order_key(float f) {
-  if (f != f) f = -INFINITY;
-  const uint32_t u = __float_as_uint(f);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
+using dev::f64_to_bf16;
+using dev::order_key;
 
 // one wavefront per unit
 __global__ __launch_bounds__(kWave) void append_kernel(const AppendArgs a) {
@@ -94,19 +92,6 @@ __global__ __launch_bounds__(kWave) void append_kernel(const AppendArgs a) {
   }
 }
 
-__device__ __forceinline__ uint16_t f64_to_bf16(double x) {
-  const uint64_t u = (uint64_t)__double_as_longlong(x);
-  const uint32_t sign = (uint32_t)(u >> 48) & 0x8000u;
-  const int e = (int)((u >> 52) & 0x7ff) - 1023 + 127;
-  if (e <= 0) return (uint16_t)sign;
-  if (e >= 255) return (uint16_t)(sign | 0x7f80u);
-  const uint64_t man = u & 0xfffffffffffffull;
-  const uint32_t top = (uint32_t)(man >> 45);
-  const uint64_t rest = man & ((1ull << 45) - 1), half = 1ull << 44;
-  uint32_t mag = ((uint32_t)e << 7) | top;
-  if (rest > half || (rest == half && (top & 1u))) mag += 1;
-  return (uint16_t)(sign | mag);
-}
 
 // Pooled key / importance of the sub-block (if any) that ends with the token just appended.
 // A sub-block j ends at token t iff t + 1 == j*ls + lk.  One workgroup of d threads per unit.

@@ -20,11 +20,15 @@
 // Logits are kept in the log2 domain: z' = (scale*log2 e) q.k + b*log2 e, p = 2^(z' - m').
 #include <cmath>
 
+#include "nosa_device.h"
 #include "nosa_internal.h"
 
 namespace nosa {
 
 namespace {
+
+using dev::row_sum;
+using dev::u32x4;
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
@@ -36,7 +40,6 @@ constexpr int kLPR = 8;     // lanes per row: 8 x 16 B = one 128-byte line
 constexpr int kRPW = kWave / kLPR;   // rows per step
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // K/V rows are read exactly once per step: stream them past the caches (non-temporal).
 __device__ __forceinline__ uint4 load_stream(const uint4* p) {
@@ -65,19 +68,6 @@ struct DecodeArgs {
   float scale_log2e;
 };
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-  const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true);
-  return x + __int_as_float(y);
-}
-
-// Sum over the 8 adjacent lanes that hold one row; every one of them receives the total.
-__device__ __forceinline__ float row_sum(float x) {
-  x = dpp_add<0xB1>(x);    // quad_perm [1,0,3,2]  : lane ^ 1
-  x = dpp_add<0x4E>(x);    // quad_perm [2,3,0,1]  : lane ^ 2
-  x = dpp_add<0x141>(x);   // row_half_mirror      : the other quad of the 8
-  return x;
-}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -286,7 +276,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
         float d = kx[i][0].dot(qv[g][0]);
 #pragma unroll
         for (int v = 1; v < VPL; ++v) d += kx[i][v].dot(qv[g][v]);
-        s[g][i] = fmaf(row_sum(d), a.scale_log2e, bl);
+        s[g][i] = fmaf(row_sum<kLPR>(d), a.scale_log2e, bl);
       }
     }
 

@@ -4,6 +4,7 @@
 // paged pool.  A block's keys and values are contiguous 8-32 KiB pieces, so every wave-load is a
 // 1 KiB contiguous read; all loads of a piece are issued before the first store so that many
 // requests are in flight on the link.  The list lengths live on the device; nothing is read back.
+#include "nosa_device.h"
 #include "nosa_internal.h"
 
 namespace nosa {
@@ -14,7 +15,7 @@ namespace {
 #endif
 constexpr int kThreads = NOSA_FETCH_THREADS;
 constexpr int kInFlight = 4;   // 16-byte loads per lane before the stores start
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using dev::u32x4;
 
 struct FetchArgs {
   const u32x4* host_k;

@@ -2,25 +2,13 @@
 // pooled keys K_c[j] = mean of the keys of sub-block j (block compression f_c of Sec. 2.1 realised
 // as the mean of the mean-pooling Eq., Sec. 3.1) and pooled importance S_c^e[j] = mean of b over it.
 // Sums run in fp64 in token order, so the stored K_c is the correctly rounded mean.
+#include "nosa_device.h"
 #include "nosa_internal.h"
 
 namespace nosa {
 namespace {
 
-// fp64 -> bf16, round to nearest even, for finite values in the normal fp32 range (or zero)
-__device__ __forceinline__ uint16_t f64_to_bf16(double x) {
-  const uint64_t u = (uint64_t)__double_as_longlong(x);
-  const uint32_t sign = (uint32_t)(u >> 48) & 0x8000u;
-  const int e = (int)((u >> 52) & 0x7ff) - 1023 + 127;     // fp32-biased exponent
-  if (e <= 0) return (uint16_t)sign;                        // below the normal range: flush to zero
-  if (e >= 255) return (uint16_t)(sign | 0x7f80u);
-  const uint64_t man = u & 0xfffffffffffffull;              // 52 bits
-  uint32_t top = (uint32_t)(man >> 45);                     // 7 kept bits
-  const uint64_t rest = man & ((1ull << 45) - 1), half = 1ull << 44;
-  uint32_t mag = ((uint32_t)e << 7) | top;
-  if (rest > half || (rest == half && (top & 1u))) mag += 1;  // carry may bump the exponent: still correct
-  return (uint16_t)(sign | mag);
-}
+using dev::f64_to_bf16;
 
 struct PoolArgs {
   const void* keys;

@@ -8,6 +8,7 @@
 // kernel: LPR adjacent lanes hold one pooled key, partial dot products are added with DPP.
 #include <cmath>
 
+#include "nosa_device.h"
 #include "nosa_internal.h"
 
 namespace nosa {
@@ -16,40 +17,9 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kBlocksPerWg = 64;
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-  const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true);
-  return x + __int_as_float(y);
-}
-
-template <int LPR>
-__device__ __forceinline__ float row_sum(float x) {
-  x = dpp_add<0xB1>(x);
-  x = dpp_add<0x4E>(x);
-  x = dpp_add<0x141>(x);
-  if constexpr (LPR >= 16) x = dpp_add<0x140>(x);
-  if constexpr (LPR >= 32) x += __shfl_xor(x, 16);
-  return x;
-}
-
-template <int DT>
-__device__ __forceinline__ void widen16(const uint4& raw, float* f);
-template <>
-__device__ __forceinline__ void widen16<NOSA_DTYPE_BF16>(const uint4& raw, float* f) {
-  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    f[2 * i] = __uint_as_float(w[i] << 16);
-    f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-  }
-}
-template <>
-__device__ __forceinline__ void widen16<NOSA_DTYPE_F32>(const uint4& raw, float* f) {
-  f[0] = __uint_as_float(raw.x);
-  f[1] = __uint_as_float(raw.y);
-  f[2] = __uint_as_float(raw.z);
-  f[3] = __uint_as_float(raw.w);
-}
+using dev::row_sum;
+using dev::u32x4;
+using dev::widen16;
 
 struct ScoreArgs {
   const void* q;
@@ -128,7 +98,6 @@ __global__ __launch_bounds__(kThreads) void block_score_kernel(const ScoreArgs a
 // Fast path for one pooled key per block (pool_kernel == pool_stride == block size): sub-block j is
 // block j, the block max is the identity.  A workgroup streams 128 pooled keys; every lane issues its
 // 8 non-temporal 16-byte loads before the first dot product.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kFastBlocksPerWg = 128;
 
 template <int DT, int D>

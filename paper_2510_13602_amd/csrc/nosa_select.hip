@@ -11,16 +11,13 @@
 // same scan yields the missed blocks, a second one over the slots yields the victims.
 #include <cmath>
 
+#include "nosa_device.h"
 #include "nosa_internal.h"
 
 namespace nosa {
 namespace {
 
-__device__ __forceinline__ uint32_t order_key(float f) {
-  if (f != f) f = -INFINITY;                     // NaN scores rank last
-  const uint32_t u = __float_as_uint(f);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);   // monotone: larger float -> larger key; always >= 0x007fffff
-}
+using dev::order_key;
 
 __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
   return __popcll(mask & ((1ull << lane) - 1ull));
