@@ -30,6 +30,7 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=0, help="distinct GPU layer states to cycle (0 = workload default, max 32)")
     ap.add_argument("--host-layers", type=int, default=2, help="distinct pinned host pools (each 8 GiB at the 8B shape)")
     ap.add_argument("--splits", type=int, default=0, help="override the number of attention splits")
+    ap.add_argument("--fetch-wgs", type=int, default=0, help="override the gather kernel's grid size")
     ap.add_argument("--no-overlap", action="store_true", help="run the fetch on the main stream")
     ap.add_argument("--resident", action="store_true", help="kernel-only mode: same queries every step, so nothing is fetched")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -295,6 +296,8 @@ def main():
     ctx = nosa.Nosa(params, stream=stream, device=dev)
     if args.splits:
         ctx.set_splits(args.splits)
+    if args.fetch_wgs:
+        ctx.set_fetch_workgroups(args.fetch_wgs)
     ctx.set_overlap(not args.no_overlap)
 
     # host pools: every block of the cache, pinned; drawn on the GPU (seeded) and copied out

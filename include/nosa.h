@@ -106,6 +106,11 @@ int nosa_get_splits(const nosa_ctx* ctx);
  * main stream in call order (used to check that both orders give the same result).               */
 int nosa_set_overlap(nosa_ctx* ctx, int overlap);
 
+/* Size of the gather kernel's persistent grid (default 512, capped by the number of units).  Each
+ * workgroup keeps 16 KiB of host reads in flight: more workgroups raise the link throughput (36 GB/s
+ * at 16, 52 at 64, 56 at 512 on PCIe Gen5 x16) but slow HBM reads of kernels that run beside it.   */
+int nosa_set_fetch_workgroups(nosa_ctx* ctx, int workgroups);
+
 const char* nosa_last_error(const nosa_ctx* ctx); /* ctx may be NULL */
 
 /* ---- the hot path (Alg. 1, one decode step of one layer) -------------------------------------*/

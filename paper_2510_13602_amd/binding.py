@@ -13,7 +13,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("NOSA_LIBRARY", os.path.join(_HERE, "libnosa.so"))   # override: experiments only
+LIB_PATH = os.path.join(_HERE, "libnosa.so")
 
 NOSA_OK, NOSA_EINVAL, NOSA_ESHAPE, NOSA_EHIP = 0, -1, -2, -3
 DTYPE_F32, DTYPE_BF16 = 0, 1
@@ -23,7 +23,7 @@ MAX_SPLITS = 16
 
 EXPORTS = [
     "nosa_validate_params", "nosa_create", "nosa_destroy", "nosa_workspace_bytes", "nosa_set_workspace",
-    "nosa_set_splits", "nosa_get_splits", "nosa_set_overlap", "nosa_last_error", "nosa_block_score",
+    "nosa_set_splits", "nosa_get_splits", "nosa_set_overlap", "nosa_set_fetch_workgroups", "nosa_last_error", "nosa_block_score",
     "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_fetch_tokens", "nosa_decode_step", "nosa_graph_create", "nosa_graph_launch",
     "nosa_graph_destroy", "nosa_timing_enable",
     "nosa_timing_read",
@@ -74,6 +74,7 @@ def load_library() -> ctypes.CDLL:
     lib.nosa_set_splits.argtypes = [vp, ctypes.c_int]
     lib.nosa_get_splits.argtypes = [vp]
     lib.nosa_set_overlap.argtypes = [vp, ctypes.c_int]
+    lib.nosa_set_fetch_workgroups.argtypes = [vp, ctypes.c_int]
     lib.nosa_last_error.argtypes = [vp]
     lib.nosa_last_error.restype = ctypes.c_char_p
     lib.nosa_block_score.argtypes = [vp, vp, vp, fp, i32p, fp, fp]
@@ -180,6 +181,9 @@ class Nosa:
 
     def set_overlap(self, on: bool) -> None:
         self._check(self.lib.nosa_set_overlap(self._ctx, 1 if on else 0))
+
+    def set_fetch_workgroups(self, n: int) -> None:
+        self._check(self.lib.nosa_set_fetch_workgroups(self._ctx, n))
 
     def timing_enable(self, on: bool) -> None:
         self._check(self.lib.nosa_timing_enable(self._ctx, 1 if on else 0))

@@ -1,7 +1,6 @@
 // C-ABI entry points of libnosa: argument validation, context, stream ordering, timing.
 // Every entry point validates before it launches; the kernels live in the other files.
 #include <cmath>
-#include <cstdlib>
 #include <new>
 
 #include "nosa_internal.h"
@@ -127,10 +126,6 @@ int nosa_create(nosa_ctx** out, const nosa_params* p, void* main_stream) {
   ctx->scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
   ctx->main = (hipStream_t)main_stream;
   ctx->splits = nosa::decode_default_splits(*p);
-  if (const char* e = getenv("NOSA_FETCH_WGS")) {   // tuning knob for experiments
-    const int v = atoi(e);
-    if (v >= 1 && v <= 65535) ctx->fetch_wgs = v;
-  }
   auto bail = [&](const char* what, hipError_t e) {
     set_error(nullptr, NOSA_EHIP, "%s failed: %s", what, hipGetErrorString(e));
     nosa_destroy(ctx);
@@ -192,6 +187,13 @@ int nosa_set_splits(nosa_ctx* ctx, int splits) {
 }
 
 int nosa_get_splits(const nosa_ctx* ctx) { return ctx ? ctx->splits : NOSA_EINVAL; }
+
+int nosa_set_fetch_workgroups(nosa_ctx* ctx, int workgroups) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, workgroups >= 1 && workgroups <= 65535, NOSA_EINVAL, "workgroups %d not in [1, 65535]", workgroups);
+  ctx->fetch_wgs = workgroups;
+  return NOSA_OK;
+}
 
 int nosa_set_overlap(nosa_ctx* ctx, int overlap) {
   NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
