@@ -36,6 +36,7 @@ def test_append_places_tokens_and_keeps_attention_and_fetch_bound():
             T0 = int(n_tok[0])
             J, row = T0 // nb, T0 % nb
             had_slot = sob[:, :, J].copy()
+            bos_before = bos.copy()
             oracle.append(p, to_np(tok["k_new"]), to_np(tok["v_new"]), to_np(tok["b_new"]), pk, pv, pb, hk, hv, hb,
                           prev_se, n_tok, sob, bos)
             assert (n_tok == T0 + 1).all()
@@ -43,6 +44,18 @@ def test_append_places_tokens_and_keeps_attention_and_fetch_bound():
             assert (hb[:, :, J, row] == to_np(tok["b_new"])).all()
             if row == 0:
                 assert (had_slot < 0).all() and (sob[:, :, J] >= 0).all()      # new block: slot without a fetch
+                for b in range(B):
+                    for h in range(H):
+                        s_new = sob[b, h, J]
+                        empty = np.nonzero(bos_before[b, h] < 0)[0]
+                        if len(empty):
+                            assert s_new == empty[0]                             # lowest empty slot first
+                        else:                                                    # else the least important candidate
+                            protect = max(w.window_blocks, 2)
+                            cand = [s for s in range(C) if w.sink_blocks <= bos_before[b, h, s] <= J - protect]
+                            want = min(cand, key=lambda s: (prev_se[b, h, bos_before[b, h, s]], s))
+                            assert s_new == want
+                            assert sob[b, h, bos_before[b, h, want]] == -1       # the evicted block lost its slot
         kc, sec = oracle.pool(p, hk, hb, n_tok)
         q = to_np(qs.next(t))
         sq, se = oracle.block_score(p, q, kc, sec, n_tok)
