@@ -178,3 +178,53 @@ def test_1b_shaped_importance_ranked_victims():
     m1 = sum(r["n_load_mean"] for r in r1[4:]) / len(r1[4:])
     print(f"1b, C=64: mean misses per unit and step, slot order {m0:.2f}, importance ranked {m1:.2f}", flush=True)
     assert m1 < m0
+
+
+@pytest.mark.parametrize("K,Kq,Ns,Nw,tokens", [(6, 2, 1, 1, [0, 1, 64, 65, 700, 768]), (1, 0, 0, 1, [1, 63, 64, 130, 500, 768]),
+                                               (4, 1, 0, 2, [0, 0, 2, 128, 129, 767])])
+def test_degenerate_token_counts_per_batch_element(K, Kq, Ns, Nw, tokens):
+    """Empty caches, a single token, exactly one block, one token into the next block, and the
+    table's capacity, all in one batch; K = 1 keeps only the tail block.  Whole step against the oracle."""
+    import oracle
+    import paper_2510_13602_amd as nosa
+    from helpers import gpu_params, oracle_params, out_tol, to_np
+    from nosa_inputs import QueryStream, make_layer
+    from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+    w = CONFIGS["tiny"].replace(batch=len(tokens), n_q_heads=8, n_kv_heads=2, context=768, k_blocks=K, kq_blocks=Kq,
+                                sink_blocks=Ns, window_blocks=Nw, gpu_slots=K + 1, dtype="bf16", head_dim=128)
+    layer = make_layer(w, 11, 0)
+    n_tok = np.array(tokens, np.int32)
+    po = oracle_params(w)
+    hk, hv, hb = to_np(layer["host_k"]), to_np(layer["host_v"]), to_np(layer["host_bias"])
+    kc, sec = oracle.pool(po, hk, hb, n_tok)
+    B, H, C, nb, d = w.batch, w.n_kv_heads, w.gpu_slots, w.block_size, w.head_dim
+    pk, pv = np.zeros((B, H, C, nb, d), hk.dtype), np.zeros((B, H, C, nb, d), hv.dtype)
+    pb = np.zeros((B, H, C, nb), np.float32)
+    sob, bos = np.full((B, H, w.max_blocks), -1, np.int32), np.full((B, H, C), -1, np.int32)
+    ctx = nosa.Nosa(gpu_params(w))
+    gl = LayerCache(ctx, pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"]),
+                    torch.from_numpy(n_tok))
+    gl.rebuild_pooled()
+    torch.cuda.synchronize()
+    assert to_np(gl.k_pooled).tobytes() == kc.tobytes()
+    gl.pool_k.fill_(float("nan")); gl.pool_v.fill_(float("nan")); gl.pool_bias.fill_(float("nan"))
+    qs = QueryStream(w, 11, 0)
+    for t in range(4):
+        q = qs.next(t)
+        sq, se = oracle.block_score(po, to_np(q), kc, sec, n_tok)
+        sel, n_sel = oracle.select(po, sq, se, n_tok)
+        ll, n_load = oracle.load(po, sel, n_sel, sob, bos)
+        oracle.fetch(po, hk, hv, hb, pk, pv, pb, ll, n_load)
+        ref, ref_lse = oracle.attention(po, to_np(q), pk, pv, pb, sel, n_sel, sob, n_tok)
+        out = gl.step(q.to("cuda:0"))
+        torch.cuda.synchronize()
+        assert (gl.sel_idx.cpu().numpy() == sel).all() and (gl.n_sel.cpu().numpy() == n_sel).all()
+        assert (gl.n_load.cpu().numpy() == n_load).all() and (gl.load_list.cpu().numpy() == ll).all()
+        got = out.double().cpu().numpy()
+        assert np.isfinite(got).all()
+        assert np.abs(got - ref).max() <= out_tol(w.dtype)
+        for b, T in enumerate(tokens):
+            if T == 0:
+                assert (got[b] == 0).all() and (n_sel[b] == 0).all()         # nothing to attend: zero rows
+                assert np.isneginf(gl.lse[b].cpu().numpy()).all()
+    ctx.close()
