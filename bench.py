@@ -39,8 +39,11 @@ def parse_args():
     ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--kq", type=int, default=0, help="override the query-aware budget Kq (blocks); Ke shrinks accordingly")
-    ap.add_argument("--study", default="", choices=["", "transfer"],
-                    help="transfer: block-wise versus element-wise host-to-device gather over miss fractions (prints one JSON line per point)")
+    ap.add_argument("--study", default="", choices=["", "transfer", "prefill"],
+                    help="transfer: block-wise versus element-wise host-to-device gather over miss fractions (prints one JSON line per point); "
+                         "prefill: sparse prefill of one chunk at the end of the 8B-shaped context (one JSON line)")
+    ap.add_argument("--prefill-batch", type=int, default=4)
+    ap.add_argument("--prefill-chunk", type=int, default=2048, help="query positions per chunk (multiple of 64)")
     ap.add_argument("--mode", default="fused", choices=["calls", "fused", "graph"],
                     help="how a step crosses the C ABI: four calls, the single nosa_decode_step entry, or a HIP graph replay")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -226,7 +229,7 @@ def longgen_bench(args):
         do_step(i)
     torch.cuda.synchronize()
     ctx.timing_enable(True)
-    for k in range(7):
+    for k in range(len(nosa.KERNEL_NAMES)):
         ctx.timing_read(k)
     t0 = time.perf_counter()
     for i in range(args.warmup, total):
@@ -248,6 +251,93 @@ def longgen_bench(args):
                    "kq_blocks": w.kq_blocks, "layers_cycled": L, "upstream": "split_qkv_evict + append every step"},
         "kernels_avg_us": kern,
         "fetch": {"mean_blocks_per_unit": float(loads.mean().item()), "max_blocks_per_unit": float(loads.max().item())},
+    }
+    ctx.close()
+    print(json.dumps(line), flush=True)
+
+
+def prefill_study(args):
+    """Sparse prefill of the last chunk of an 8B-shaped context: every query position selects its blocks
+    (score + selection kernels on a virtual batch of positions) and attends to them on the matrix cores.
+    A step is one chunk (batch x chunk positions) of one layer; two cache copies alternate."""
+    import torch
+    import paper_2510_13602_amd as nosa
+    from nosa_inputs import CONFIGS, chunk_queries, make_layer
+    dev = "cuda:0"
+    B, lq = args.prefill_batch, args.prefill_chunk
+    w = CONFIGS["8b"].replace(batch=B)
+    w = w.replace(gpu_slots=w.max_blocks)
+    p0 = w.context - lq
+    H, Hq, d, K = w.n_kv_heads, w.n_q_heads, w.head_dim, w.k_blocks
+    stream = torch.cuda.Stream(device=dev)
+    torch.cuda.set_stream(stream)
+    params = nosa.make_params(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, k_blocks=K, kq_blocks=w.kq_blocks,
+                              sink_blocks=w.sink_blocks, window_blocks=w.window_blocks, gpu_slots=w.gpu_slots,
+                              max_blocks=w.max_blocks, n_sub_max=w.n_sub_max, dtype=w.dtype)
+    ctx = nosa.Nosa(params, stream=stream, device=dev)
+    td = w.torch_dtype
+    L = 2
+    caches, qs = [], []
+    n_full = torch.full((B,), w.context, dtype=torch.int32, device=dev)
+    for l in range(L):
+        lay = make_layer(w, args.seed, l, device=dev)
+        kc = torch.zeros((B, H, w.n_sub_max, d), dtype=td, device=dev)
+        sec = torch.zeros((B, H, w.n_sub_max), dtype=torch.float32, device=dev)
+        ctx.nosa_pool_blocks(lay["host_k"], lay["host_bias"], n_full, kc, sec)
+        caches.append((lay["host_k"], lay["host_v"], lay["host_bias"], kc, sec))
+        qs.append(chunk_queries(w, args.seed, l, lq, device=dev).to(td))
+    n_tok_s = torch.empty((B * lq,), dtype=torch.int32, device=dev)
+    sq_s = torch.empty((B, lq, H, w.max_blocks), dtype=torch.float32, device=dev)
+    se_s = torch.empty_like(sq_s)
+    sel = torch.empty((B, lq, H, K), dtype=torch.int32, device=dev)
+    n_sel = torch.empty((B, lq, H), dtype=torch.int32, device=dev)
+    out = torch.empty((B, lq, Hq, d), dtype=td, device=dev)
+    lse = torch.empty((B, lq, Hq), dtype=torch.float32, device=dev)
+
+    def do_step(i):
+        ck, cv, cb, kc, sec = caches[i % L]
+        q = qs[i % L]
+        ctx.nosa_prefill_select(q, kc, sec, p0, lq, n_tok_s, sq_s, se_s, sel, n_sel)
+        ctx.nosa_prefill_attend(q, ck, cv, cb, sel, n_sel, p0, lq, out, lse)
+
+    for i in range(args.warmup):
+        do_step(i)
+    torch.cuda.synchronize()
+    ctx.timing_enable(True)
+    for k in range(len(nosa.KERNEL_NAMES)):
+        ctx.timing_read(k)
+    t0 = time.perf_counter()
+    for i in range(args.warmup, args.warmup + args.steps):
+        do_step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.timing_enable(False)
+    kern = {}
+    for k, name in enumerate(nosa.KERNEL_NAMES):
+        ms, n = ctx.timing_read(k)
+        if n:
+            kern[name] = 1e3 * ms / n
+    # algorithmic work of the attention kernel: 4 d flops per (query head, attended token)
+    t_in_blk = (torch.arange(lq, device=dev) % 64).view(1, lq, 1)
+    tokens = (n_sel.long() * 64 - (63 - t_in_blk)).sum().item()
+    flops = 4.0 * d * w.group * tokens
+    s4 = sel.view(B, lq // 64, 64, H, K).permute(0, 1, 3, 2, 4).reshape(B, lq // 64, H, 64 * K).long()
+    member = torch.zeros((B, lq // 64, H, w.max_blocks + 1), dtype=torch.bool, device=dev)
+    member.scatter_(3, torch.where(s4 >= 0, s4, torch.full_like(s4, w.max_blocks)), True)
+    union = member[..., :w.max_blocks].sum(-1).float()
+    t_att = kern["prefill_attend"] * 1e-6
+    line = {
+        "metric": "sparse prefill tokens/sec (selection + attention of one layer)", "value": B * lq * args.steps / dt,
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "8b-shaped sparse prefill, last chunk", "batch": B, "chunk": lq, "p0": p0, "n_q_heads": Hq,
+                   "n_kv_heads": H, "head_dim": d, "context": w.context, "k_blocks": K, "kq_blocks": w.kq_blocks,
+                   "sink_blocks": w.sink_blocks, "window_blocks": w.window_blocks},
+        "roofline": {"bound": "mfma", "achieved": flops / t_att / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": flops / t_att / 2.5e15, "traffic": None,
+                     "kernel": "prefill_attend", "kernel_avg_us": kern["prefill_attend"], "flops_per_launch": flops},
+        "kernels_avg_us": kern,
+        "union_blocks_per_workgroup": {"mean": float(union.mean().item()), "max": float(union.max().item()), "budget": K},
     }
     ctx.close()
     print(json.dumps(line), flush=True)
@@ -278,6 +368,8 @@ def main():
         return
     if args.study == "transfer":
         return transfer_study(args)
+    if args.study == "prefill":
+        return prefill_study(args)
     if args.workload == "longgen":
         return longgen_bench(args)
     w = CONFIGS[args.workload]

@@ -243,6 +243,29 @@ int nosa_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float
                 void* k_pooled, float* se_pooled, const float* se_blk, int32_t* n_tokens,
                 int32_t* slot_of_block, int32_t* block_of_slot);
 
+/* ---- sparse prefill (sparse attention in both stages; results Table, "Sparse Prefill" rows) ---
+ *
+ * A chunk of lq query positions p0 .. p0+lq-1 per batch element, whose keys, values and biases are
+ * already in the cache and whose complete blocks are already pooled (nosa_pool_blocks).  Position t
+ * of the chunk behaves like a decode step with n_tokens = p0 + t + 1: the same scores, the same
+ * constrained selection (selection Eq., Sec. 3.1), the same biased softmax (Sec. 3.2) over the
+ * selected tokens, none of which is in its future.  Nothing is offloaded during prefill, so the
+ * cache is addressed by block: cache_k, cache_v [B,Hkv,max_blocks,n_b,d], cache_bias
+ * [B,Hkv,max_blocks,n_b] fp32 (the pool layout with slot = block; needs gpu_slots == max_blocks).
+ * Restrictions: bf16, p0 and lq multiples of n_b = 64, p0 + lq <= max_blocks * n_b.  All pointers dev.
+ *
+ * nosa_prefill_select: q_chunk [B,lq,Hq,d] -> sel_idx [B,lq,Hkv,K] (ascending, -1 padded) and n_sel
+ * [B,lq,Hkv].  Scratch owned by the caller: n_tok_scratch int32 [B*lq], sq_scratch and se_scratch
+ * fp32 [B*lq*Hkv*max_blocks] (they hold the per-position block scores afterwards).
+ *
+ * nosa_prefill_attend: out [B,lq,Hq,d] (dtype) and lse [B,lq,Hq] fp32 from the selection above.  */
+int nosa_prefill_select(nosa_ctx* ctx, const void* q_chunk, const void* k_pooled, const float* se_pooled,
+                        int32_t p0, int32_t lq, int32_t* n_tok_scratch, float* sq_scratch, float* se_scratch,
+                        int32_t* sel_idx, int32_t* n_sel);
+int nosa_prefill_attend(nosa_ctx* ctx, const void* q_chunk, const void* cache_k, const void* cache_v,
+                        const float* cache_bias, const int32_t* sel_idx, const int32_t* n_sel, int32_t p0,
+                        int32_t lq, void* out, float* lse);
+
 /* ---- per-kernel timing for benchmarks --------------------------------------------------------*/
 
 #define NOSA_KERNEL_SCORE 0
@@ -252,7 +275,8 @@ int nosa_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float
 #define NOSA_KERNEL_COMBINE 4 /* merge of split results, or the second (fetched blocks + merge) launch */
 #define NOSA_KERNEL_EVICT 5   /* nosa_split_qkv_evict                                           */
 #define NOSA_KERNEL_APPEND 6  /* the launches of nosa_append together                           */
-#define NOSA_KERNEL_COUNT 7
+#define NOSA_KERNEL_PREFILL 7 /* the attention kernel of nosa_prefill_attend                    */
+#define NOSA_KERNEL_COUNT 8
 /* When enabled, each launch of the kernels above is bracketed by HIP events on the stream it runs
  * on.  nosa_timing_read synchronises those events, returns the summed duration and the number of
  * launches since the last read, and resets the counters.  At most 4096 launches per kernel are

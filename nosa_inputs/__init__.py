@@ -260,6 +260,22 @@ class QueryStream:
         return self.commit(self.draw(step))
 
 
+def chunk_queries(w: Workload, seed: int, layer: int, lq: int, retry: int = 0, device="cpu") -> torch.Tensor:
+    """Queries of a prefill chunk, fp32 [B, lq, Hq, d]: q_t = 3 u + x_t with x_t AR(1) along the positions
+    (rho = 0.9), u the unit direction of the KV head -- neighbouring positions look for similar blocks, as
+    neighbouring tokens of a text do.  ``retry`` gives an independent draw of the same law.
+    """
+    u = unit_directions(w, seed, layer, device).repeat_interleave(w.group, dim=1)      # [B,Hq,d]
+    eps = torch.randn((lq, w.batch, w.n_q_heads, w.head_dim), generator=_gen(device, seed, _T_Q, layer, 1 << 20, retry),
+                      device=device, dtype=torch.float32)
+    x = torch.empty_like(eps)
+    x[0] = eps[0]
+    c = math.sqrt(1 - 0.81)
+    for t in range(1, lq):
+        x[t] = 0.9 * x[t - 1] + c * eps[t]
+    return (3.0 * u.unsqueeze(0) + x).permute(1, 0, 2, 3).contiguous()
+
+
 def append_token(w: Workload, seed: int, layer: int, step: int, device="cpu") -> dict:
     """Key, value and bias of the token appended at ``step`` (growing-context workload).
 

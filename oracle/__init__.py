@@ -300,7 +300,8 @@ def fetch_tokens(p: Params, host_k, host_v, host_bias, pool_k, pool_v, pool_bias
                               _ptr(pool_bias), _ptr(token_list), _ptr(n_list), ctypes.c_int(M))
 
 
-def prefill(p: Params, q_chunk: np.ndarray, cache_k, cache_v, cache_bias, k_pooled, se_pooled, p0: int):
+def prefill(p: Params, q_chunk: np.ndarray, cache_k, cache_v, cache_bias, k_pooled, se_pooled, p0: int,
+            positions=None):
     """Sparse prefill of a chunk of query tokens (NOSA with sparse prefill: the mask Eq. of Sec. 2.1 with the
     selection Eq. of Sec. 3.1 evaluated at every query position).
 
@@ -309,18 +310,19 @@ def prefill(p: Params, q_chunk: np.ndarray, cache_k, cache_v, cache_bias, k_pool
     positions < p0 + Lq.  Position p0 + t sees T = p0 + t + 1 tokens: its output is, by definition, the
     decode step's output on a cache of those T tokens -- so this function is a plain loop over positions
     calling block_score, select and attention, with every block resident (slot = block index).
-    Returns sel [B,Hkv,Lq,K], n_sel [B,Hkv,Lq], out [B,Lq,Hq,d] fp64, lse [B,Lq,Hq].
+    Returns sel [B,Hkv,Lq,K], n_sel [B,Hkv,Lq], out [B,Lq,Hq,d] fp64, lse [B,Lq,Hq].  ``positions`` (chunk
+    offsets t) limits the loop to a sample; the rows of the other positions are left at -1 / NaN.
     """
     B, H, d = p.batch, p.n_kv_heads, p.head_dim
     Lq = q_chunk.shape[1]
     _check(q_chunk, (B, Lq, p.n_q_heads, d), p.np_dtype, "q_chunk")
     assert p.gpu_slots == p.max_blocks, "prefill runs on a fully resident cache: gpu_slots must equal max_blocks"
     ident = np.tile(np.arange(p.max_blocks, dtype=np.int32), (B, H, 1))
-    sel_all = np.empty((B, H, Lq, p.k_blocks), np.int32)
-    nsel_all = np.empty((B, H, Lq), np.int32)
-    out_all = np.empty((B, Lq, p.n_q_heads, d), np.float64)
-    lse_all = np.empty((B, Lq, p.n_q_heads), np.float64)
-    for t in range(Lq):
+    sel_all = np.full((B, H, Lq, p.k_blocks), -1, np.int32)
+    nsel_all = np.full((B, H, Lq), -1, np.int32)
+    out_all = np.full((B, Lq, p.n_q_heads, d), np.nan, np.float64)
+    lse_all = np.full((B, Lq, p.n_q_heads), np.nan, np.float64)
+    for t in (range(Lq) if positions is None else positions):
         n_tok = np.full((B,), p0 + t + 1, np.int32)
         q = np.ascontiguousarray(q_chunk[:, t])
         sq, se = block_score(p, q, k_pooled, se_pooled, n_tok)

@@ -18,14 +18,14 @@ LIB_PATH = os.path.join(_HERE, "libnosa.so")
 NOSA_OK, NOSA_EINVAL, NOSA_ESHAPE, NOSA_EHIP = 0, -1, -2, -3
 DTYPE_F32, DTYPE_BF16 = 0, 1
 KERNEL_SCORE, KERNEL_SELECT, KERNEL_FETCH, KERNEL_DECODE, KERNEL_COMBINE, KERNEL_EVICT, KERNEL_APPEND = range(7)
-KERNEL_NAMES = ["block_score", "select", "fetch", "sparse_decode", "combine", "split_qkv_evict", "append"]
+KERNEL_NAMES = ["block_score", "select", "fetch", "sparse_decode", "combine", "split_qkv_evict", "append", "prefill_attend"]
 MAX_SPLITS = 16
 
 EXPORTS = [
     "nosa_validate_params", "nosa_create", "nosa_destroy", "nosa_workspace_bytes", "nosa_set_workspace",
     "nosa_set_splits", "nosa_get_splits", "nosa_set_overlap", "nosa_set_fetch_workgroups", "nosa_last_error", "nosa_block_score",
     "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_fetch_tokens", "nosa_decode_step", "nosa_graph_create", "nosa_graph_launch",
-    "nosa_graph_destroy", "nosa_timing_enable",
+    "nosa_graph_destroy", "nosa_prefill_select", "nosa_prefill_attend", "nosa_timing_enable",
     "nosa_timing_read",
 ]
 
@@ -294,6 +294,31 @@ class Nosa:
             _dev(w1, torch.float32, (d, H), "w1"), _dev(w2, torch.float32, (H,), "w2"), int(mode),
             _dev(q_out, self.tdtype, (B, p.n_q_heads, d), "q_out"), _dev(k_new, self.tdtype, (B, H, d), "k_new"),
             _dev(v_new, self.tdtype, (B, H, d), "v_new"), _dev(b_new, torch.float32, (B, H), "b_new")))
+
+    def nosa_prefill_select(self, q_chunk, k_pooled, se_pooled, p0, lq, n_tok_scratch, sq_scratch, se_scratch, sel_idx,
+                            n_sel) -> None:
+        p, B, H = self.p, self._B, self._H
+        self._check(self.lib.nosa_prefill_select(
+            self._ctx, _dev(q_chunk, self.tdtype, (B, lq, p.n_q_heads, p.head_dim), "q_chunk"),
+            _dev(k_pooled, self.tdtype, (B, H, p.n_sub_max, p.head_dim), "k_pooled"),
+            _dev(se_pooled, torch.float32, (B, H, p.n_sub_max), "se_pooled"), int(p0), int(lq),
+            _dev(n_tok_scratch, torch.int32, (B * lq,), "n_tok_scratch"),
+            _dev(sq_scratch, torch.float32, (B, lq, H, p.max_blocks), "sq_scratch"),
+            _dev(se_scratch, torch.float32, (B, lq, H, p.max_blocks), "se_scratch"),
+            _dev(sel_idx, torch.int32, (B, lq, H, p.k_blocks), "sel_idx"),
+            _dev(n_sel, torch.int32, (B, lq, H), "n_sel")))
+
+    def nosa_prefill_attend(self, q_chunk, cache_k, cache_v, cache_bias, sel_idx, n_sel, p0, lq, out, lse) -> None:
+        p, B, H = self.p, self._B, self._H
+        kv = (B, H, p.max_blocks, p.block_size, p.head_dim)
+        self._check(self.lib.nosa_prefill_attend(
+            self._ctx, _dev(q_chunk, self.tdtype, (B, lq, p.n_q_heads, p.head_dim), "q_chunk"),
+            _dev(cache_k, self.tdtype, kv, "cache_k"), _dev(cache_v, self.tdtype, kv, "cache_v"),
+            _dev(cache_bias, torch.float32, kv[:4], "cache_bias"),
+            _dev(sel_idx, torch.int32, (B, lq, H, p.k_blocks), "sel_idx"),
+            _dev(n_sel, torch.int32, (B, lq, H), "n_sel"), int(p0), int(lq),
+            _dev(out, self.tdtype, (B, lq, p.n_q_heads, p.head_dim), "out"),
+            _dev(lse, torch.float32, (B, lq, p.n_q_heads), "lse")))
 
     def step_args(self, q, k_pooled, se_pooled, n_tokens, sq_blk, se_blk, sel_idx, n_sel, slot_of_block, block_of_slot,
                   load_list, n_load, host_k, host_v, host_bias, pool_k, pool_v, pool_bias, out, lse=None) -> StepArgs:

@@ -233,6 +233,51 @@ int nosa_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const i
   return NOSA_OK;
 }
 
+static int prefill_check(nosa_ctx* ctx, const char* who, int p0, int lq) {
+  const nosa_params& p = ctx->p;
+  NOSA_REQUIRE(ctx, p.dtype == NOSA_DTYPE_BF16, NOSA_ESHAPE, "%s: the prefill path is bf16 only", who);
+  NOSA_REQUIRE(ctx, p.gpu_slots == p.max_blocks, NOSA_ESHAPE,
+               "%s: the cache is addressed by block, gpu_slots (%d) must equal max_blocks (%d)", who, p.gpu_slots,
+               p.max_blocks);
+  NOSA_REQUIRE(ctx, p0 >= 0 && lq > 0 && p0 % p.block_size == 0 && lq % p.block_size == 0, NOSA_ESHAPE,
+               "%s: p0 (%d) and lq (%d) must be multiples of the block size, lq > 0", who, p0, lq);
+  NOSA_REQUIRE(ctx, (long long)p0 + lq <= (long long)p.max_blocks * p.block_size, NOSA_ESHAPE,
+               "%s: p0 + lq = %lld exceeds the cache (%lld tokens)", who, (long long)p0 + lq,
+               (long long)p.max_blocks * p.block_size);
+  NOSA_REQUIRE(ctx, (long long)p.batch * lq * p.n_kv_heads <= (1 << 24), NOSA_ESHAPE,
+               "%s: B * lq * Hkv = %lld exceeds %d positions x KV heads per call: split the chunk", who,
+               (long long)p.batch * lq * p.n_kv_heads, 1 << 24);
+  return NOSA_OK;
+}
+
+int nosa_prefill_select(nosa_ctx* ctx, const void* q_chunk, const void* k_pooled, const float* se_pooled,
+                        int32_t p0, int32_t lq, int32_t* n_tok_scratch, float* sq_scratch, float* se_scratch,
+                        int32_t* sel_idx, int32_t* n_sel) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, q_chunk && k_pooled && se_pooled && n_tok_scratch && sq_scratch && se_scratch && sel_idx && n_sel,
+               NOSA_EINVAL, "nosa_prefill_select: NULL argument");
+  int rc = prefill_check(ctx, "nosa_prefill_select", p0, lq);
+  if (rc != NOSA_OK) return rc;
+  // every position is a batch element of its own that shares the pooled keys of its sequence
+  rc = nosa::launch_prefill_positions(ctx, n_tok_scratch, p0, lq);
+  if (rc != NOSA_OK) return rc;
+  rc = nosa::launch_block_score(ctx, q_chunk, k_pooled, se_pooled, n_tok_scratch, sq_scratch, se_scratch, lq);
+  if (rc != NOSA_OK) return rc;
+  return nosa::launch_select(ctx, sq_scratch, se_scratch, n_tok_scratch, sel_idx, n_sel, nullptr, nullptr, nullptr,
+                             nullptr, lq);
+}
+
+int nosa_prefill_attend(nosa_ctx* ctx, const void* q_chunk, const void* cache_k, const void* cache_v,
+                        const float* cache_bias, const int32_t* sel_idx, const int32_t* n_sel, int32_t p0,
+                        int32_t lq, void* out, float* lse) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, q_chunk && cache_k && cache_v && cache_bias && sel_idx && n_sel && out && lse, NOSA_EINVAL,
+               "nosa_prefill_attend: NULL argument");
+  int rc = prefill_check(ctx, "nosa_prefill_attend", p0, lq);
+  if (rc != NOSA_OK) return rc;
+  return nosa::launch_prefill_attend(ctx, q_chunk, cache_k, cache_v, cache_bias, sel_idx, n_sel, p0, lq, out, lse);
+}
+
 int nosa_fetch(nosa_ctx* ctx, const void* host_k, const void* host_v, const float* host_bias,
                void* pool_k, void* pool_v, float* pool_bias, const int32_t* load_list, const int32_t* n_load) {
   NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");

@@ -79,10 +79,14 @@ struct TimedLaunch {
 
 // kernel launchers (one per translation unit); all validate nothing: callers have done so
 int launch_block_score(nosa_ctx* ctx, const void* q, const void* k_pooled, const float* se_pooled,
-                       const int32_t* n_tokens, float* sq_blk, float* se_blk);
+                       const int32_t* n_tokens, float* sq_blk, float* se_blk, int batch_div = 1);
 int launch_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const int32_t* n_tokens,
                   int32_t* sel_idx, int32_t* n_sel, int32_t* slot_of_block, int32_t* block_of_slot,
-                  int32_t* load_list, int32_t* n_load);
+                  int32_t* load_list, int32_t* n_load, int batch_mul = 1);
+int launch_prefill_positions(nosa_ctx* ctx, int32_t* n_tok_virtual, int p0, int lq);
+int launch_prefill_attend(nosa_ctx* ctx, const void* q_chunk, const void* cache_k, const void* cache_v,
+                          const float* cache_bias, const int32_t* sel_idx, const int32_t* n_sel, int p0, int lq,
+                          void* out, float* lse);
 int launch_fetch(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const void* host_v,
                  const float* host_bias, void* pool_k, void* pool_v, float* pool_bias,
                  const int32_t* load_list, const int32_t* n_load);

@@ -29,6 +29,8 @@ struct ScoreArgs {
   float* sq_blk;
   float* se_blk;
   int n_kv_heads, group, max_blocks, n_sub_max, pool_kernel, pool_stride;
+  int batch_div;   // virtual batch elements (query positions of a prefill chunk) per cache batch element; 1 in decode
+  int n_units;     // (virtual batch element, KV head) pairs; they are folded over grid y and z
 };
 
 template <int DT, int D>
@@ -40,8 +42,10 @@ __global__ __launch_bounds__(kThreads) void block_score_kernel(const ScoreArgs a
   constexpr int GROUPS = (kThreads / kWave) * RPW;   // row-groups per workgroup
   constexpr int ITERS = kBlocksPerWg / GROUPS;
 
-  const int unit = blockIdx.y;
+  const int unit = blockIdx.z * gridDim.y + blockIdx.y;         // (virtual batch element, KV head)
+  if (unit >= a.n_units) return;
   const int b = unit / a.n_kv_heads, h = unit % a.n_kv_heads;
+  const int cache_unit = (b / a.batch_div) * a.n_kv_heads + h;    // where its pooled keys live
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int r = lane / LPR, c = lane % LPR;
   const int T = a.n_tokens[b];
@@ -63,8 +67,8 @@ __global__ __launch_bounds__(kThreads) void block_score_kernel(const ScoreArgs a
     }
   }
 
-  const uint4* kc = (const uint4*)((const char*)a.k_pooled + (size_t)unit * a.n_sub_max * D * ES);
-  const float* sec = a.se_pooled + (size_t)unit * a.n_sub_max;
+  const uint4* kc = (const uint4*)((const char*)a.k_pooled + (size_t)cache_unit * a.n_sub_max * D * ES);
+  const float* sec = a.se_pooled + (size_t)cache_unit * a.n_sub_max;
   const int J0 = blockIdx.x * kBlocksPerWg;
 
 #pragma unroll
@@ -109,15 +113,17 @@ __global__ __launch_bounds__(kThreads) void block_score_simple_kernel(const Scor
   constexpr int GROUPS = (kThreads / kWave) * RPW;
   constexpr int ITERS = kFastBlocksPerWg / GROUPS;
 
-  const int unit = blockIdx.y;
+  const int unit = blockIdx.z * gridDim.y + blockIdx.y;         // (virtual batch element, KV head)
+  if (unit >= a.n_units) return;
   const int b = unit / a.n_kv_heads, h = unit % a.n_kv_heads;
+  const int cache_unit = (b / a.batch_div) * a.n_kv_heads + h;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int r = lane / LPR, c = lane % LPR;
   const int nsub = min(a.n_tokens[b] / kBlockTokens, a.n_sub_max);   // complete blocks
   const int J0 = blockIdx.x * kFastBlocksPerWg + wave * RPW + r;     // this lane's row in round 0
 
-  const u32x4* kc = (const u32x4*)((const char*)a.k_pooled + (size_t)unit * a.n_sub_max * D * ES);
-  const float* sec = a.se_pooled + (size_t)unit * a.n_sub_max;
+  const u32x4* kc = (const u32x4*)((const char*)a.k_pooled + (size_t)cache_unit * a.n_sub_max * D * ES);
+  const float* sec = a.se_pooled + (size_t)cache_unit * a.n_sub_max;
   u32x4 kv[ITERS];
   float sev[ITERS];
 #pragma unroll
@@ -163,13 +169,14 @@ __global__ __launch_bounds__(kThreads) void block_score_simple_kernel(const Scor
 }  // namespace
 
 int launch_block_score(nosa_ctx* ctx, const void* q, const void* k_pooled, const float* se_pooled,
-                       const int32_t* n_tokens, float* sq_blk, float* se_blk) {
+                       const int32_t* n_tokens, float* sq_blk, float* se_blk, int batch_div) {
   const nosa_params& p = ctx->p;
   ScoreArgs a{q, k_pooled, se_pooled, n_tokens, sq_blk, se_blk, p.n_kv_heads, ctx->group,
-              p.max_blocks, p.n_sub_max, p.pool_kernel, p.pool_stride};
+              p.max_blocks, p.n_sub_max, p.pool_kernel, p.pool_stride, batch_div, ctx->units * batch_div};
+  const int gz = (a.n_units + 32767) / 32768, gy = (a.n_units + gz - 1) / gz;   // grid y and z stay below 65536
   TimedLaunch tl(ctx, NOSA_KERNEL_SCORE, ctx->main);
   if (p.pool_kernel == p.block_size && p.pool_stride == p.block_size) {
-    const dim3 fgrid((p.max_blocks + kFastBlocksPerWg - 1) / kFastBlocksPerWg, ctx->units);
+    const dim3 fgrid((p.max_blocks + kFastBlocksPerWg - 1) / kFastBlocksPerWg, gy, gz);
     if (p.dtype == NOSA_DTYPE_BF16) {
       if (p.head_dim == 128) hipLaunchKernelGGL((block_score_simple_kernel<NOSA_DTYPE_BF16, 128>), fgrid, dim3(kThreads), 0, ctx->main, a);
       else hipLaunchKernelGGL((block_score_simple_kernel<NOSA_DTYPE_BF16, 64>), fgrid, dim3(kThreads), 0, ctx->main, a);
@@ -180,7 +187,7 @@ int launch_block_score(nosa_ctx* ctx, const void* q, const void* k_pooled, const
     NOSA_HIP(ctx, hipGetLastError());
     return NOSA_OK;
   }
-  const dim3 grid((p.max_blocks + kBlocksPerWg - 1) / kBlocksPerWg, ctx->units);
+  const dim3 grid((p.max_blocks + kBlocksPerWg - 1) / kBlocksPerWg, gy, gz);
   if (p.dtype == NOSA_DTYPE_BF16) {
     if (p.head_dim == 128) hipLaunchKernelGGL((block_score_kernel<NOSA_DTYPE_BF16, 128>), grid, dim3(kThreads), 0, ctx->main, a);
     else hipLaunchKernelGGL((block_score_kernel<NOSA_DTYPE_BF16, 64>), grid, dim3(kThreads), 0, ctx->main, a);

@@ -121,6 +121,21 @@ __global__ __launch_bounds__(kWave) void select_kernel(const SelectArgs a) {
 
   // Gamma(t) ascending; misses = selected blocks without a slot
   int32_t* sel = a.sel_idx + (size_t)unit * K;
+  if (a.slot_of_block == nullptr) {   // selection only (prefill: every block is resident)
+    int n_on = 0;
+    for (int base = 0; base < N; base += kWave) {
+      const int J = base + lane;
+      const bool on = J < N && flags[J] != 0;
+      const uint64_t m = __ballot(on);
+      const int pos = n_on + lanes_below(m, lane);
+      if (on && pos < K) sel[pos] = J;
+      n_on += (int)__popcll(m);
+    }
+    n_on = min(n_on, K);
+    for (int i = n_on + lane; i < K; i += kWave) sel[i] = -1;
+    if (lane == 0) a.n_sel[unit] = n_on;
+    return;
+  }
   int32_t* sob = a.slot_of_block + (size_t)unit * a.max_blocks;
   int32_t* bos = a.block_of_slot + (size_t)unit * a.gpu_slots;
   int n_sel = 0, n_miss = 0;
@@ -203,7 +218,7 @@ __global__ __launch_bounds__(kWave) void select_kernel(const SelectArgs a) {
 
 int launch_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const int32_t* n_tokens,
                   int32_t* sel_idx, int32_t* n_sel, int32_t* slot_of_block, int32_t* block_of_slot,
-                  int32_t* load_list, int32_t* n_load) {
+                  int32_t* load_list, int32_t* n_load, int batch_mul) {
   const nosa_params& p = ctx->p;
   SelectArgs a{sq_blk, se_blk, n_tokens, sel_idx, n_sel, slot_of_block, block_of_slot, load_list, n_load,
                p.n_kv_heads, p.max_blocks, p.k_blocks, p.kq_blocks, p.sink_blocks, p.window_blocks, p.gpu_slots,
@@ -213,7 +228,7 @@ int launch_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const
   const int R = regs <= 8 ? 8 : regs <= 16 ? 16 : regs <= 32 ? 32 : 64;
   NOSA_REQUIRE(ctx, regs <= 64, NOSA_ESHAPE, "selection supports at most %d blocks per unit", kMaxSelectBlocks);
   const size_t smem = (size_t)p.k_blocks * 8 + 2 * (size_t)R * kWave;
-  const dim3 grid(ctx->units), block(kWave);
+  const dim3 grid(ctx->units * batch_mul), block(kWave);   // batch_mul > 1: one virtual batch element per query position
   TimedLaunch tl(ctx, NOSA_KERNEL_SELECT, ctx->main);
   switch (R) {
     case 8: hipLaunchKernelGGL(select_kernel<8>, grid, block, smem, ctx->main, a); break;

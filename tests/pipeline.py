@@ -302,3 +302,82 @@ def run_growing(w: Workload, seed: int, steps: int, device="cuda:0", margin=1e-3
     assert to_np(gl.host_bias).tobytes() == ol.hb.tobytes()
     ctx.close()
     return dict(worst=worst, boundary_loads=boundary_loads)
+
+
+# ---- sparse prefill --------------------------------------------------------------------------------
+
+def prefill_inputs(w: Workload, seed: int, p0: int, lq: int, positions=None, margin: float = 1e-3, max_retry: int = 8):
+    """Cache, pooled arrays and the chunk's queries.  Positions (all, or the sample) whose query-aware selection
+    margin is below ``margin`` get the query of an independent redraw, unit by unit."""
+    from nosa_inputs import chunk_queries
+    p = oracle_params(w)
+    layer = make_layer(w, seed, 0)
+    hk, hv, hb = to_np(layer["host_k"]), to_np(layer["host_v"]), to_np(layer["host_bias"])
+    n_full = np.full((w.batch,), p0 + lq, np.int32)
+    kc, sec = oracle.pool(p, hk, hb, n_full)
+    q32 = chunk_queries(w, seed, 0, lq)
+    pos = list(range(lq)) if positions is None else list(positions)
+    G = w.group
+    todo = pos
+    for r in range(1, max_retry + 1):
+        q = to_np(q32.to(w.torch_dtype))
+        bad = []
+        for t in todo:
+            n_tok = np.full((w.batch,), p0 + t + 1, np.int32)
+            sq, _ = oracle.block_score(p, np.ascontiguousarray(q[:, t]), kc, sec, n_tok)
+            for b, h in np.argwhere(query_margin(w, sq, n_tok) < margin):
+                bad.append((t, b, h))
+        if not bad:
+            break
+        alt = chunk_queries(w, seed, 0, lq, retry=r)
+        for t, b, h in bad:
+            q32[b, t, h * G:(h + 1) * G] = alt[b, t, h * G:(h + 1) * G]
+        todo = sorted({t for t, _, _ in bad})
+    else:
+        raise AssertionError("selection margin not reached")
+    return dict(p=p, hk=hk, hv=hv, hb=hb, kc=kc, sec=sec, q=q32.to(w.torch_dtype), layer=layer)
+
+
+def run_prefill_parity(w: Workload, seed: int, p0: int, lq: int, positions=None, device="cuda:0"):
+    """One chunk through oracle.prefill and through nosa_prefill_select / nosa_prefill_attend: selections
+    bit-exact, outputs within the dtype's tolerance, at all positions or at the sample."""
+    import paper_2510_13602_amd as nosa
+    inp = prefill_inputs(w, seed, p0, lq, positions)
+    p = inp["p"]
+    q_np = to_np(inp["q"])
+    sel_o, nsel_o, out_o, lse_o = oracle.prefill(p, q_np, inp["hk"], inp["hv"], inp["hb"], inp["kc"], inp["sec"], p0,
+                                                 positions)
+    B, H, d = w.batch, w.n_kv_heads, w.head_dim
+    td = w.torch_dtype
+    ctx = nosa.Nosa(gpu_params(w), device=device)
+    ck, cv = inp["layer"]["host_k"].to(device), inp["layer"]["host_v"].to(device)
+    cb = inp["layer"]["host_bias"].to(device)
+    n_full = torch.full((B,), p0 + lq, dtype=torch.int32, device=device)
+    kc = torch.zeros((B, H, w.n_sub_max, d), dtype=td, device=device)
+    sec = torch.zeros((B, H, w.n_sub_max), dtype=torch.float32, device=device)
+    ctx.nosa_pool_blocks(ck, cb, n_full, kc, sec)
+    q = inp["q"].to(device)
+    n_tok_s = torch.empty((B * lq,), dtype=torch.int32, device=device)
+    sq_s = torch.empty((B, lq, H, w.max_blocks), dtype=torch.float32, device=device)
+    se_s = torch.empty_like(sq_s)
+    sel = torch.full((B, lq, H, w.k_blocks), -7, dtype=torch.int32, device=device)
+    n_sel = torch.full((B, lq, H), -7, dtype=torch.int32, device=device)
+    out = torch.full((B, lq, w.n_q_heads, d), float("nan"), dtype=td, device=device)
+    lse = torch.full((B, lq, w.n_q_heads), float("nan"), dtype=torch.float32, device=device)
+    ctx.nosa_prefill_select(q, kc, sec, p0, lq, n_tok_s, sq_s, se_s, sel, n_sel)
+    ctx.nosa_prefill_attend(q, ck, cv, cb, sel, n_sel, p0, lq, out, lse)
+    torch.cuda.synchronize()
+    sel_g = sel.cpu().numpy().transpose(0, 2, 1, 3)          # -> [B,H,lq,K]
+    nsel_g = n_sel.cpu().numpy().transpose(0, 2, 1)
+    out_g, lse_g = out.float().cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+    pos = np.arange(lq) if positions is None else np.asarray(sorted(positions))
+    np.testing.assert_array_equal(n_tok_s.cpu().numpy().reshape(B, lq), np.tile(p0 + np.arange(lq) + 1, (B, 1)))
+    np.testing.assert_array_equal(nsel_g[:, :, pos], nsel_o[:, :, pos])
+    np.testing.assert_array_equal(sel_g[:, :, pos], sel_o[:, :, pos])
+    tol = out_tol(w.dtype)
+    err = np.abs(out_g[:, pos] - out_o[:, pos]).max()
+    assert np.isfinite(out_g).all() and err <= tol, f"prefill attention: max abs err {err} > {tol}"
+    lerr = np.abs(lse_g[:, pos] - lse_o[:, pos]).max()
+    assert lerr <= 1e-2, f"prefill lse: max abs err {lerr}"
+    ctx.close()
+    return dict(err=err, lse_err=lerr, n_pos=len(pos))
