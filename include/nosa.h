@@ -256,7 +256,9 @@ int nosa_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float
  *
  * nosa_prefill_select: q_chunk [B,lq,Hq,d] -> sel_idx [B,lq,Hkv,K] (ascending, -1 padded) and n_sel
  * [B,lq,Hkv].  Scratch owned by the caller: n_tok_scratch int32 [B*lq], sq_scratch and se_scratch
- * fp32 [B*lq*Hkv*max_blocks] (they hold the per-position block scores afterwards).
+ * fp32 [B*lq*Hkv*max_blocks].  Afterwards sq_scratch holds the query-aware block scores of every
+ * position for the complete blocks of its prefix (other entries unspecified); se_scratch is only
+ * written when the pooling windows differ from the blocks (pool_kernel or pool_stride != n_b).
  *
  * nosa_prefill_attend: out [B,lq,Hq,d] (dtype) and lse [B,lq,Hq] fp32 from the selection above.  */
 int nosa_prefill_select(nosa_ctx* ctx, const void* q_chunk, const void* k_pooled, const float* se_pooled,

@@ -261,6 +261,15 @@ int nosa_prefill_select(nosa_ctx* ctx, const void* q_chunk, const void* k_pooled
   // every position is a batch element of its own that shares the pooled keys of its sequence
   rc = nosa::launch_prefill_positions(ctx, n_tok_scratch, p0, lq);
   if (rc != NOSA_OK) return rc;
+  const nosa_params& p = ctx->p;
+  if (p.pool_kernel == p.block_size && p.pool_stride == p.block_size) {
+    // one pooled key per block: scores as one matrix product per unit; the block-level importance of a
+    // complete block is its pooled importance, so the selection reads se_pooled itself
+    rc = nosa::launch_prefill_score(ctx, q_chunk, k_pooled, sq_scratch, p0, lq);
+    if (rc != NOSA_OK) return rc;
+    return nosa::launch_select(ctx, sq_scratch, se_pooled, n_tok_scratch, sel_idx, n_sel, nullptr, nullptr, nullptr,
+                               nullptr, lq, lq, p.n_sub_max);
+  }
   rc = nosa::launch_block_score(ctx, q_chunk, k_pooled, se_pooled, n_tok_scratch, sq_scratch, se_scratch, lq);
   if (rc != NOSA_OK) return rc;
   return nosa::launch_select(ctx, sq_scratch, se_scratch, n_tok_scratch, sel_idx, n_sel, nullptr, nullptr, nullptr,

@@ -82,7 +82,9 @@ int launch_block_score(nosa_ctx* ctx, const void* q, const void* k_pooled, const
                        const int32_t* n_tokens, float* sq_blk, float* se_blk, int batch_div = 1);
 int launch_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const int32_t* n_tokens,
                   int32_t* sel_idx, int32_t* n_sel, int32_t* slot_of_block, int32_t* block_of_slot,
-                  int32_t* load_list, int32_t* n_load, int batch_mul = 1);
+                  int32_t* load_list, int32_t* n_load, int batch_mul = 1, int se_unit_div = 1,
+                  int se_stride = 0);
+int launch_prefill_score(nosa_ctx* ctx, const void* q_chunk, const void* k_pooled, float* sq, int p0, int lq);
 int launch_prefill_positions(nosa_ctx* ctx, int32_t* n_tok_virtual, int p0, int lq);
 int launch_prefill_attend(nosa_ctx* ctx, const void* q_chunk, const void* cache_k, const void* cache_v,
                           const float* cache_bias, const int32_t* sel_idx, const int32_t* n_sel, int p0, int lq,

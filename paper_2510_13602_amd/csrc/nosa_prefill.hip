@@ -3,14 +3,15 @@
 // causal prefix (selection Eq. of Sec. 3.1) and attends, with the eviction-head bias (Sec. 3.2),
 // to the tokens of its selected blocks that are not in its future.
 //
-// Unlike the decode step this is a dense contraction per selected block (64 positions x G heads
+// Unlike the decode step this is a dense contraction per selected block (32 positions x G heads
 // of queries against 64 keys), so it runs on the matrix cores: v_mfma_f32_32x32x16_bf16, fp32
 // accumulation, flash-style online softmax.
 //
-// One workgroup = 64 consecutive query positions of one (batch element, KV head), one wave = one
-// query head.  Positions that are neighbours select mostly the same blocks, so the workgroup walks
-// the UNION of their selections once; a 64-bit membership word per block says which positions
-// take part.  Per visited block:
+// One workgroup = 32 consecutive query positions of one (batch element, KV head), one wave = one
+// query head; two workgroups fit a CU (<= 256 registers per lane), so one's tile loads hide under
+// the other's arithmetic.  Positions that are neighbours select mostly the same blocks, so the
+// workgroup walks the UNION of their selections once; a 32-bit membership word per block says
+// which positions take part.  Per visited block:
 //   S^T = K Q^T        A = K tile from LDS, B = Q^T held in registers for the whole kernel.
 //                      In the C layout a lane owns ONE query (column) and 16 keys per 32x32 tile,
 //                      so row max / row sum are in-lane plus one exchange with lane ^ 32.
@@ -21,7 +22,12 @@
 //                      swapped) and no cross-lane traffic is needed.
 // V arrives from HBM as [key][d]; it is transposed on its way into LDS (two keys packed per
 // 32-bit store).  Both LDS tiles are XOR-swizzled in 16-byte chunks so that the 16-byte operand
-// reads of eight neighbouring lanes fall into different banks.
+// reads of eight neighbouring lanes fall into different banks.  The next block's rows are fetched
+// into registers while the current block is being multiplied.
+//
+// Workgroups are numbered so that the 64 that run together on one XCD (32 CUs x 2) are
+// neighbouring query tiles of the same (batch element, KV head): they share most of their
+// blocks (the query-agnostic picks and overlapping windows), which then come from that XCD's L2.
 #include <cmath>
 
 #include "nosa_device.h"
@@ -32,11 +38,14 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 using dev::u32x4;
 
 constexpr int kThreads = 256;
-constexpr int kQ = 64;            // query positions per workgroup
+constexpr int kQ = 32;            // query positions per workgroup
 constexpr int kHeadsPerWg = 4;    // one wave each
+constexpr int kXcds = 8;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -50,6 +59,7 @@ struct PrefillArgs {
   void* out;                 // [B, Lq, Hq, d]
   float* lse;                // [B, Lq, Hq]
   int n_kv_heads, group, n_q_heads, max_blocks, k_blocks, p0, lq;
+  int units, n_qt, n_hz, list_cap;   // B*Hkv, query tiles per unit, head quads per KV head, LDS list capacity
   float scale;
 };
 
@@ -58,208 +68,324 @@ __global__ void prefill_positions_kernel(int32_t* n_tok, int p0, int lq, int tot
   if (i < total) n_tok[i] = p0 + i % lq + 1;   // position t of a chunk sees p0 + t + 1 tokens
 }
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // round to nearest even; finite inputs
-  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-  a += 0x7fffu + ((a >> 16) & 1u);
-  b += 0x7fffu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xffff0000u);
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // round to nearest even (v_cvt_pk_bf16_f32)
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 template <int D>
-__global__ __launch_bounds__(kThreads) void prefill_attend_kernel(const PrefillArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const PrefillArgs a) {
   constexpr int CH = D / 8;     // 16-byte chunks per key row
   constexpr int KC = D / 16;    // k-steps of the score product
   constexpr int RD = D / 32;    // 32-row tiles of O^T
   constexpr int kRowK = D * 2;  // bytes per row of the K tile
   constexpr int kRowV = 128;    // bytes per row of the V^T tile (64 keys)
+  constexpr int KR = kBlockTokens * CH / kThreads;         // 16-byte K loads per thread and tile
+  constexpr int VR = (kBlockTokens / 2) * CH / kThreads;   // key pairs of V per thread and tile
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* Ks = smem;                                   // [64 keys][D] swizzled
   unsigned char* Vt = Ks + 64 * kRowK;                        // [D][64 key positions] swizzled
   float* bias_s = (float*)(Vt + D * kRowV);                   // [64], already times log2(e)
-  unsigned long long* memb = (unsigned long long*)(bias_s + 64);   // [blocks up to the diagonal]
+  int* n_list_s = (int*)(bias_s + 64);                        // [4] (one used)
+  uint32_t* memb = (uint32_t*)(n_list_s + 4);                 // [list_cap] bit t: position t selected the block
+  int* list_j = (int*)(memb + a.list_cap);                    // [list_cap] visited blocks, ascending
+  uint32_t* list_m = (uint32_t*)(list_j + a.list_cap);        // [list_cap] their membership words
 
-  const int qb = blockIdx.x;
-  const int unit = blockIdx.y;   // b * Hkv + h
+  // workgroup -> (unit, query tile, head quad): id % 8 is the XCD the hardware dispatches to
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int hz = slot % a.n_hz, qt = (slot / a.n_hz) % a.n_qt;
+  const int unit = xcd + kXcds * (slot / (a.n_hz * a.n_qt));   // b * Hkv + h
+  if (unit >= a.units) return;                                 // before any barrier
   const int b = unit / a.n_kv_heads, h = unit % a.n_kv_heads;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-  const int g = blockIdx.z * kHeadsPerWg + wave;
+  const int g = hz * kHeadsPerWg + wave;
   const bool active = g < a.group;      // wave-uniform
   const int hq = h * a.group + (active ? g : 0);
   const int l32 = lane % 32, hb = lane / 32;
-  const int diag = a.p0 / kBlockTokens + qb;   // the block these 64 positions live in
+  const int t0 = qt * kQ;                              // first chunk position of this tile
+  const int diag = (a.p0 + t0) / kBlockTokens;         // the block these positions live in
+  const int toff = (a.p0 + t0) % kBlockTokens + l32;   // this lane's query, as a row of that block
   const int nblk = diag + 1;
   const float scale2 = a.scale * kLog2e;
 
-  // membership words: bit t of memb[J] = position t of this workgroup selected block J
-  for (int J = tid; J < nblk; J += kThreads) memb[J] = 0ull;
+  for (int J = tid; J < nblk; J += kThreads) memb[J] = 0u;
   __syncthreads();
   {
     const int K = a.k_blocks;
     for (int idx = tid; idx < kQ * K; idx += kThreads) {
       const int t = idx / K, k = idx - t * K;
-      const size_t vu = ((size_t)b * a.lq + qb * kQ + t) * a.n_kv_heads + h;
+      const size_t vu = ((size_t)b * a.lq + t0 + t) * a.n_kv_heads + h;
       if (k < a.n_sel[vu]) {
         const int J = a.sel_idx[vu * K + k];
-        if (J >= 0 && J < nblk) atomicOr(&memb[J], 1ull << t);
+        if (J >= 0 && J < nblk) atomicOr(&memb[J], 1u << t);
       }
     }
   }
 
-  // Q^T operands, resident for the whole kernel: lane = (query l32 of column tile ct, k half hb)
-  bf16x8 qreg[2][KC];
-#pragma unroll
-  for (int ct = 0; ct < 2; ++ct) {
-    const size_t row = ((size_t)b * a.lq + qb * kQ + ct * 32 + l32) * a.n_q_heads + hq;
+  // Q^T operand, resident for the whole kernel: lane = (query l32, k half hb)
+  bf16x8 qreg[KC];
+  {
+    const size_t row = ((size_t)b * a.lq + t0 + l32) * a.n_q_heads + hq;
     const u32x4* qp = (const u32x4*)((const char*)a.q + row * (size_t)(D * 2));
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) qreg[ct][kc] = __builtin_bit_cast(bf16x8, qp[2 * kc + hb]);
+    for (int kc = 0; kc < KC; ++kc) qreg[kc] = __builtin_bit_cast(bf16x8, qp[2 * kc + hb]);
   }
+  __syncthreads();
+  if (wave == 0) {   // the visited blocks, ascending
+    int n = 0;
+    for (int base = 0; base < nblk; base += kWave) {
+      const int J = base + lane;
+      const uint32_t m = J < nblk ? memb[J] : 0u;
+      const uint64_t bal = __ballot(m != 0u);
+      if (m != 0u) {
+        const int pos = n + (int)__popcll(bal & ((1ull << lane) - 1ull));
+        list_j[pos] = J;
+        list_m[pos] = m;
+      }
+      n += (int)__popcll(bal);
+    }
+    if (lane == 0) n_list_s[0] = n;
+  }
+  __syncthreads();
+  const int n_list = n_list_s[0];
 
-  f32x16 o[RD][2];
+  f32x16 o[RD];
 #pragma unroll
   for (int rd = 0; rd < RD; ++rd)
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[rd][ct][i] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY};   // running max, in log2 units
-  float l_run[2] = {0.f, 0.f};               // this lane's share of the running sum
-  __syncthreads();
+    for (int i = 0; i < 16; ++i) o[rd][i] = 0.f;
+  float m_run = -INFINITY;   // running max, in log2 units
+  float l_run = 0.f;         // this lane's share of the running sum
 
-  for (int J = 0; J < nblk; ++J) {
-    const unsigned long long mb = memb[J];   // same word for every thread: uniform branch
-    if (mb == 0ull) continue;
-    __syncthreads();                         // the previous tile has been consumed
-
-    const size_t blk = (size_t)unit * a.max_blocks + J;
+  const size_t unit_blk = (size_t)unit * a.max_blocks;
+  u32x4 kpre[KR], vpre0[VR], vpre1[VR];
+  float bpre = 0.f;
+  auto fetch_tile = [&](int J) {   // global -> registers
+    const size_t blk = unit_blk + J;
     const char* kg = (const char*)a.cache_k + blk * (size_t)(kBlockTokens * kRowK);
     const char* vg = (const char*)a.cache_v + blk * (size_t)(kBlockTokens * kRowK);
-    for (int i = tid; i < kBlockTokens * CH; i += kThreads) {
-      const int key = i / CH, c = i % CH;
-      const u32x4 v = *(const u32x4*)(kg + (size_t)i * 16);
-      *(u32x4*)(Ks + key * kRowK + ((c ^ (key & 7)) * 16)) = v;
+#pragma unroll
+    for (int r = 0; r < KR; ++r) kpre[r] = *(const u32x4*)(kg + (size_t)(tid + r * kThreads) * 16);
+#pragma unroll
+    for (int r = 0; r < VR; ++r) {
+      const int i = tid + r * kThreads;
+      const int key = 2 * (i / CH), e = i % CH;
+      vpre0[r] = *(const u32x4*)(vg + ((size_t)key * CH + e) * 16);
+      vpre1[r] = *(const u32x4*)(vg + ((size_t)(key + 1) * CH + e) * 16);
     }
-    for (int i = tid; i < (kBlockTokens / 2) * CH; i += kThreads) {
-      const int pr = i / CH, e = i % CH;
-      const int key = 2 * pr;
-      const u32x4 v0 = *(const u32x4*)(vg + ((size_t)key * CH + e) * 16);
-      const u32x4 v1 = *(const u32x4*)(vg + ((size_t)(key + 1) * CH + e) * 16);
+    if (tid < kBlockTokens) bpre = a.cache_bias[blk * kBlockTokens + tid];
+  };
+  auto stage_tile = [&]() {        // registers -> LDS (K swizzled, V transposed and swizzled)
+#pragma unroll
+    for (int r = 0; r < KR; ++r) {
+      const int i = tid + r * kThreads;
+      const int key = i / CH, c = i % CH;
+      *(u32x4*)(Ks + key * kRowK + ((c ^ (key & 7)) * 16)) = kpre[r];
+    }
+#pragma unroll
+    for (int r = 0; r < VR; ++r) {
+      const int i = tid + r * kThreads;
+      const int key = 2 * (i / CH), e = i % CH;
       const int pos = (key & ~0xC) | ((key & 8) >> 1) | ((key & 4) << 1);   // even; key + 1 sits at pos + 1
       const int chunk = (pos >> 3) ^ (e & 7);
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const uint32_t a0 = v0[w], a1 = v1[w];
+        const uint32_t a0 = vpre0[r][w], a1 = vpre1[r][w];
         const int dd = 8 * e + 2 * w;
         *(uint32_t*)(Vt + dd * kRowV + ((chunk ^ (dd & 7)) * 16) + (pos & 7) * 2) = (a0 & 0xffffu) | (a1 << 16);
         *(uint32_t*)(Vt + (dd + 1) * kRowV + ((chunk ^ ((dd + 1) & 7)) * 16) + (pos & 7) * 2) =
             (a0 >> 16) | (a1 & 0xffff0000u);
       }
     }
-    if (tid < kBlockTokens) bias_s[tid] = a.cache_bias[blk * kBlockTokens + tid] * kLog2e;
+    if (tid < kBlockTokens) bias_s[tid] = bpre * kLog2e;
+  };
+
+  if (n_list > 0) fetch_tile(list_j[0]);
+  for (int it = 0; it < n_list; ++it) {
+    const int J = list_j[it];
+    const uint32_t mb = list_m[it];
+    stage_tile();
     __syncthreads();
+    if (it + 1 < n_list) fetch_tile(list_j[it + 1]);   // in flight during the arithmetic below
 
     if (active) {
-      f32x16 s[2][2];   // [key tile][query tile]
+      f32x16 s[2];   // two tiles of 32 keys
 #pragma unroll
       for (int rk = 0; rk < 2; ++rk)
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) s[rk][ct][i] = 0.f;
+        for (int i = 0; i < 16; ++i) s[rk][i] = 0.f;
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) {
 #pragma unroll
         for (int rk = 0; rk < 2; ++rk) {
           const int key = rk * 32 + l32;
           const bf16x8 ak = *(const bf16x8*)(Ks + key * kRowK + (((2 * kc + hb) ^ (key & 7)) * 16));
-          s[rk][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qreg[0][kc], s[rk][0], 0, 0, 0);
-          s[rk][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qreg[1][kc], s[rk][1], 0, 0, 0);
+          s[rk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qreg[kc], s[rk], 0, 0, 0);
         }
       }
 
-      const bool is_diag = J == diag;
-      bf16x8 pb[2][4];   // P^T operands [query tile][k-step of 16 keys]
+      // accumulator i of key tile rk is key rk*32 + 8*(i/4) + 4*hb + i%4
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        const int t = ct * 32 + l32;
-        const bool member = (mb >> t) & 1ull;
-        float mx = -INFINITY;
+      for (int rk = 0; rk < 2; ++rk)
 #pragma unroll
-        for (int rk = 0; rk < 2; ++rk) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int kidx = rk * 32 + 8 * (i / 4) + 4 * hb + (i % 4);   // key of accumulator i
-            float z = fmaf(s[rk][ct][i], scale2, bias_s[kidx]);
-            if (is_diag && kidx > t) z = -INFINITY;                     // the future
-            s[rk][ct][i] = z;
-            mx = fmaxf(mx, z);
-          }
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const float4 bz = *(const float4*)(bias_s + rk * 32 + 8 * i4 + 4 * hb);
+          s[rk][4 * i4 + 0] = fmaf(s[rk][4 * i4 + 0], scale2, bz.x);
+          s[rk][4 * i4 + 1] = fmaf(s[rk][4 * i4 + 1], scale2, bz.y);
+          s[rk][4 * i4 + 2] = fmaf(s[rk][4 * i4 + 2], scale2, bz.z);
+          s[rk][4 * i4 + 3] = fmaf(s[rk][4 * i4 + 3], scale2, bz.w);
         }
-        if (!member) mx = -INFINITY;
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[ct], mx);
-        // positions outside the block's membership, and ones that have seen nothing yet, add zeros
-        const float sub = (member && m_new != -INFINITY) ? m_new : INFINITY;
-        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run[ct] - m_new);
-        float psum = 0.f;
-        uint32_t packed[16];
+      if (J == diag) {   // the future
 #pragma unroll
-        for (int rk = 0; rk < 2; ++rk) {
+        for (int rk = 0; rk < 2; ++rk)
 #pragma unroll
-          for (int i = 0; i < 16; i += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(s[rk][ct][i] - sub);
-            const float p1 = __builtin_amdgcn_exp2f(s[rk][ct][i + 1] - sub);
-            psum += p0 + p1;
-            packed[rk * 8 + i / 2] = pack_bf16(p0, p1);
-          }
+          for (int i = 0; i < 16; ++i)
+            if (rk * 32 + 8 * (i / 4) + 4 * hb + (i % 4) > toff) s[rk][i] = -INFINITY;
+      }
+      const bool member = (mb >> l32) & 1u;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int rk = 0; rk < 2; ++rk)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[rk][i]);
+      if (!member) mx = -INFINITY;
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx);
+      // positions outside the block's membership, and ones that have seen nothing yet, add zeros
+      const float sub = (member && m_new != -INFINITY) ? m_new : INFINITY;
+      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
+      float psum = 0.f;
+      uint32_t packed[16];
+#pragma unroll
+      for (int rk = 0; rk < 2; ++rk) {
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(s[rk][i] - sub);
+          const float p1 = __builtin_amdgcn_exp2f(s[rk][i + 1] - sub);
+          psum += p0 + p1;
+          packed[rk * 8 + i / 2] = pack_bf16(p0, p1);
         }
-        l_run[ct] = l_run[ct] * alpha + psum;
-        m_run[ct] = m_new;
+      }
+      l_run = l_run * alpha + psum;
+      m_run = m_new;
+      if (__any(alpha != 1.f)) {
 #pragma unroll
         for (int rd = 0; rd < RD; ++rd)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) o[rd][ct][i] *= alpha;
-#pragma unroll
-        for (int kc = 0; kc < 4; ++kc) {
-          const u32x4 w = {packed[4 * kc], packed[4 * kc + 1], packed[4 * kc + 2], packed[4 * kc + 3]};
-          pb[ct][kc] = __builtin_bit_cast(bf16x8, w);
-        }
+          for (int i = 0; i < 16; ++i) o[rd][i] *= alpha;
       }
-
 #pragma unroll
       for (int kc = 0; kc < 4; ++kc) {
+        const u32x4 w = {packed[4 * kc], packed[4 * kc + 1], packed[4 * kc + 2], packed[4 * kc + 3]};
+        const bf16x8 pb = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
         for (int rd = 0; rd < RD; ++rd) {
           const int dd = rd * 32 + l32;
           const bf16x8 av =
               *(const bf16x8*)(Vt + dd * kRowV + ((((2 * kc + hb) ^ ((dd >> 3) & 7)) ^ (dd & 7)) * 16));
-          o[rd][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pb[0][kc], o[rd][0], 0, 0, 0);
-          o[rd][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pb[1][kc], o[rd][1], 0, 0, 0);
+          o[rd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pb, o[rd], 0, 0, 0);
         }
       }
     }
+    __syncthreads();   // the tile has been consumed
   }
 
   if (active) {
+    float l = l_run;
+    l += __shfl_xor(l, 32);
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    const size_t row = ((size_t)b * a.lq + t0 + l32) * a.n_q_heads + hq;
+    char* op = (char*)a.out + row * (size_t)(D * 2);
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
-      float l = l_run[ct];
-      l += __shfl_xor(l, 32);
-      const float inv = l > 0.f ? 1.f / l : 0.f;
-      const size_t row = ((size_t)b * a.lq + qb * kQ + ct * 32 + l32) * a.n_q_heads + hq;
-      char* op = (char*)a.out + row * (size_t)(D * 2);
+    for (int rd = 0; rd < RD; ++rd) {
 #pragma unroll
-      for (int rd = 0; rd < RD; ++rd) {
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const int dd = rd * 32 + 8 * i4 + 4 * hb;   // accumulators 4*i4 .. 4*i4+3 are dd .. dd+3
-          uint2 w;
-          w.x = pack_bf16(o[rd][ct][4 * i4] * inv, o[rd][ct][4 * i4 + 1] * inv);
-          w.y = pack_bf16(o[rd][ct][4 * i4 + 2] * inv, o[rd][ct][4 * i4 + 3] * inv);
-          *(uint2*)(op + dd * 2) = w;
-        }
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int dd = rd * 32 + 8 * i4 + 4 * hb;   // accumulators 4*i4 .. 4*i4+3 are dd .. dd+3
+        uint2 w;
+        w.x = pack_bf16(o[rd][4 * i4] * inv, o[rd][4 * i4 + 1] * inv);
+        w.y = pack_bf16(o[rd][4 * i4 + 2] * inv, o[rd][4 * i4 + 3] * inv);
+        *(uint2*)(op + dd * 2) = w;
       }
-      if (hb == 0) a.lse[row] = l > 0.f ? m_run[ct] * kLn2 + logf(l) : -INFINITY;
+    }
+    if (hb == 0) a.lse[row] = l > 0.f ? m_run * kLn2 + logf(l) : -INFINITY;
+  }
+}
+
+
+// Block scores of a whole chunk as one matrix product per (batch element, KV head), for one pooled
+// key per block (Alg. 1 Stage 1 with pool kernel = stride = block size): sq[t, J] = sum over the G
+// query heads of q_{t,g} . kc_J.  The group sum is folded into the contraction (k runs over g and
+// d), so every product is an exact bf16 x bf16 product accumulated in fp32, as in the decode path.
+// A = Q rows from LDS (staged once per workgroup), B = pooled keys straight from global memory: both
+// have the contraction index contiguous, nothing is transposed.  A workgroup = 32 positions x up to
+// 512 blocks (one wave per 128); only the entries the selection reads (complete blocks of the
+// position's prefix) are computed and written.
+struct PrefillScoreArgs {
+  const void* q;          // [B, Lq, Hq, d]
+  const void* k_pooled;   // [B, Hkv, n_sub_max, d]
+  float* sq;              // [B, Lq, Hkv, max_blocks]
+  int n_kv_heads, group, n_q_heads, max_blocks, n_sub_max, p0, lq;
+};
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void prefill_score_kernel(const PrefillScoreArgs a) {
+  constexpr int CH = D / 8, KC = D / 16, kRow = D * 2;
+  extern __shared__ __align__(16) unsigned char smem[];   // [G][32 positions][D] swizzled
+  const int tt = blockIdx.x, unit = blockIdx.y;
+  const int b = unit / a.n_kv_heads, h = unit % a.n_kv_heads;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int l32 = lane % 32, hb = lane / 32;
+  const int t0 = tt * 32;
+  const int n_hi = min((a.p0 + t0 + 32) / kBlockTokens, a.n_sub_max);   // complete blocks seen by the tile's last position
+  if ((int)blockIdx.z * 512 >= n_hi) return;                            // whole workgroup: nothing to score
+
+  const int rows = a.group * 32;
+  for (int i = tid; i < rows * CH; i += kThreads) {
+    const int r = i / CH, c = i % CH;          // r = g * 32 + position
+    const int g = r / 32, tl = r % 32;
+    const size_t row = ((size_t)b * a.lq + t0 + tl) * a.n_q_heads + h * a.group + g;
+    *(u32x4*)(smem + r * kRow + ((c ^ (r & 7)) * 16)) = *(const u32x4*)((const char*)a.q + row * (size_t)kRow + c * 16);
+  }
+  __syncthreads();
+
+  const int J0 = (blockIdx.z * 4 + wave) * 128;
+  if (J0 >= n_hi) return;                      // no barrier below
+  const char* kc = (const char*)a.k_pooled + (size_t)unit * a.n_sub_max * kRow;
+  f32x16 acc[4];
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[jt][i] = 0.f;
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt) {
+    if (J0 + jt * 32 >= n_hi) break;           // wave-uniform
+    const int J = J0 + jt * 32 + l32;
+    bf16x8 kb[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (J < n_hi) v = *(const u32x4*)(kc + (size_t)J * kRow + (2 * k + hb) * 16);
+      kb[k] = __builtin_bit_cast(bf16x8, v);
+    }
+    for (int g = 0; g < a.group; ++g) {
+      const int r = g * 32 + l32;
+#pragma unroll
+      for (int k = 0; k < KC; ++k) {
+        const bf16x8 qa = *(const bf16x8*)(smem + r * kRow + (((2 * k + hb) ^ (r & 7)) * 16));
+        acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kb[k], acc[jt], 0, 0, 0);
+      }
+    }
+  }
+  // accumulator i: position 8*(i/4) + 4*hb + i%4 of the tile, block = this lane's column
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt) {
+    const int J = J0 + jt * 32 + l32;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int tl = 8 * (i / 4) + 4 * hb + (i % 4);
+      const int nsub = min((a.p0 + t0 + tl + 1) / kBlockTokens, a.n_sub_max);
+      if (J < nsub)
+        a.sq[(((size_t)b * a.lq + t0 + tl) * a.n_kv_heads + h) * a.max_blocks + J] = acc[jt][i];
     }
   }
 }
@@ -274,18 +400,36 @@ int launch_prefill_positions(nosa_ctx* ctx, int32_t* n_tok_virtual, int p0, int 
   return NOSA_OK;
 }
 
+int launch_prefill_score(nosa_ctx* ctx, const void* q_chunk, const void* k_pooled, float* sq, int p0, int lq) {
+  const nosa_params& p = ctx->p;
+  PrefillScoreArgs a{q_chunk, k_pooled, sq, p.n_kv_heads, ctx->group, p.n_q_heads, p.max_blocks, p.n_sub_max, p0, lq};
+  const int n_hi = (p0 + lq) / kBlockTokens;
+  const dim3 grid(lq / 32, ctx->units, (n_hi + 511) / 512);
+  const size_t smem = (size_t)ctx->group * 32 * p.head_dim * 2;
+  NOSA_REQUIRE(ctx, smem <= 64 * 1024, NOSA_ESHAPE, "prefill: %d query heads per KV head need %zu bytes of LDS", ctx->group, smem);
+  NOSA_REQUIRE(ctx, ctx->units <= 65535 && grid.z <= 65535, NOSA_ESHAPE, "prefill: B * Hkv = %d exceeds 65535", ctx->units);
+  TimedLaunch tl(ctx, NOSA_KERNEL_SCORE, ctx->main);
+  if (p.head_dim == 128) hipLaunchKernelGGL(prefill_score_kernel<128>, grid, dim3(kThreads), smem, ctx->main, a);
+  else hipLaunchKernelGGL(prefill_score_kernel<64>, grid, dim3(kThreads), smem, ctx->main, a);
+  NOSA_HIP(ctx, hipGetLastError());
+  return NOSA_OK;
+}
+
 int launch_prefill_attend(nosa_ctx* ctx, const void* q_chunk, const void* cache_k, const void* cache_v,
                           const float* cache_bias, const int32_t* sel_idx, const int32_t* n_sel, int p0, int lq,
                           void* out, float* lse) {
   const nosa_params& p = ctx->p;
+  const int n_qt = lq / kQ, n_hz = (ctx->group + kHeadsPerWg - 1) / kHeadsPerWg;
+  const int list_cap = (p0 + lq) / kBlockTokens;
   PrefillArgs a{q_chunk, cache_k, cache_v, cache_bias, sel_idx, n_sel, out, lse, p.n_kv_heads, ctx->group,
-                p.n_q_heads, p.max_blocks, p.k_blocks, p0, lq, ctx->scale};
-  const int nblk_max = (p0 + lq) / kBlockTokens;
-  const size_t smem = (size_t)kBlockTokens * p.head_dim * 2 + (size_t)p.head_dim * 128 + 64 * sizeof(float) +
-                      (size_t)nblk_max * sizeof(unsigned long long);
+                p.n_q_heads, p.max_blocks, p.k_blocks, p0, lq, ctx->units, n_qt, n_hz, list_cap, ctx->scale};
+  const size_t smem = (size_t)kBlockTokens * p.head_dim * 2 + (size_t)p.head_dim * 128 + 64 * sizeof(float) + 16 +
+                      (size_t)list_cap * 12;
   NOSA_REQUIRE(ctx, smem <= 64 * 1024, NOSA_ESHAPE, "prefill: %d blocks of context need %zu bytes of LDS (limit 65536)",
-               nblk_max, smem);
-  const dim3 grid(lq / kQ, ctx->units, (ctx->group + kHeadsPerWg - 1) / kHeadsPerWg);
+               list_cap, smem);
+  const long long wgs = (long long)kXcds * ((ctx->units + kXcds - 1) / kXcds) * n_qt * n_hz;
+  NOSA_REQUIRE(ctx, wgs <= 0x7fffffffLL, NOSA_ESHAPE, "prefill: too many workgroups (%lld)", wgs);
+  const dim3 grid((unsigned)wgs);
   TimedLaunch tl(ctx, NOSA_KERNEL_PREFILL, ctx->main);
   if (p.head_dim == 128) hipLaunchKernelGGL(prefill_attend_kernel<128>, grid, dim3(kThreads), smem, ctx->main, a);
   else hipLaunchKernelGGL(prefill_attend_kernel<64>, grid, dim3(kThreads), smem, ctx->main, a);

@@ -76,6 +76,7 @@ struct SelectArgs {
   int32_t* load_list;
   int32_t* n_load;
   int n_kv_heads, max_blocks, k_blocks, kq_blocks, sink_blocks, window_blocks, gpu_slots, victim_policy;
+  int se_unit_div, se_stride;   // row of se_blk a unit reads: ((b / se_unit_div) * Hkv + h) * se_stride
 };
 
 // R = ceil(max_blocks / 64): candidate keys per lane, register resident.
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(kWave) void select_kernel(const SelectArgs a) {
   const int N = (T + kBlockTokens - 1) / kBlockTokens;
   const int Nc = T / kBlockTokens;
   const float* sq = a.sq_blk + (size_t)unit * a.max_blocks;
-  const float* se = a.se_blk + (size_t)unit * a.max_blocks;
+  const float* se = a.se_blk + ((size_t)(b / a.se_unit_div) * a.n_kv_heads + unit % a.n_kv_heads) * a.se_stride;
 
   // forced blocks and candidate keys
   const int win_lo = N - a.window_blocks;
@@ -218,11 +219,11 @@ __global__ __launch_bounds__(kWave) void select_kernel(const SelectArgs a) {
 
 int launch_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const int32_t* n_tokens,
                   int32_t* sel_idx, int32_t* n_sel, int32_t* slot_of_block, int32_t* block_of_slot,
-                  int32_t* load_list, int32_t* n_load, int batch_mul) {
+                  int32_t* load_list, int32_t* n_load, int batch_mul, int se_unit_div, int se_stride) {
   const nosa_params& p = ctx->p;
   SelectArgs a{sq_blk, se_blk, n_tokens, sel_idx, n_sel, slot_of_block, block_of_slot, load_list, n_load,
                p.n_kv_heads, p.max_blocks, p.k_blocks, p.kq_blocks, p.sink_blocks, p.window_blocks, p.gpu_slots,
-               p.victim_policy};
+               p.victim_policy, se_unit_div, se_stride > 0 ? se_stride : p.max_blocks};
   int regs = (p.max_blocks + kWave - 1) / kWave;
   if (p.victim_policy == 1 && (p.gpu_slots + kWave - 1) / kWave > regs) regs = (p.gpu_slots + kWave - 1) / kWave;
   const int R = regs <= 8 ? 8 : regs <= 16 ? 16 : regs <= 32 ? 32 : 64;

@@ -24,6 +24,8 @@ pytestmark = pytest.mark.gpu
     ("d128_g6", dict(n_q_heads=12, n_kv_heads=2, head_dim=128, k_blocks=8, kq_blocks=3, window_blocks=1), 64 * 5, 64 * 4),
     ("d64_g8", dict(n_q_heads=16, n_kv_heads=2, head_dim=64, k_blocks=10, kq_blocks=2, window_blocks=3), 64 * 20, 64 * 4),
     ("d128_g4_one_wg", dict(batch=1, n_q_heads=4, n_kv_heads=1, head_dim=128, k_blocks=5, kq_blocks=1, window_blocks=1), 64 * 9, 64),
+    ("overlapping_pool_windows", dict(n_q_heads=8, n_kv_heads=2, head_dim=128, k_blocks=8, kq_blocks=2, window_blocks=2,
+                                      pool_kernel=32, pool_stride=16), 64 * 6, 64 * 4),
     ("budget_covers_all", dict(n_q_heads=8, n_kv_heads=2, head_dim=128, k_blocks=10, kq_blocks=4, window_blocks=2), 0, 64 * 8),
 ])
 def test_prefill_parity(name, kw, p0, lq):
