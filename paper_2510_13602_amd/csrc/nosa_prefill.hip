@@ -42,12 +42,16 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 using dev::u32x4;
 
-constexpr int kThreads = 256;
-constexpr int kQ = 32;            // query positions per workgroup
-constexpr int kHeadsPerWg = 4;    // one wave each
+constexpr int kThreads = 512;     // attention kernel: 8 waves
+constexpr int kQ = 64;            // query positions per workgroup
+constexpr int kHeadsPerWg = 4;    // two waves each (32 positions per wave)
 constexpr int kXcds = 8;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+#ifndef NOSA_LAZY
+#define NOSA_LAZY 0.f
+#endif
+constexpr float kLazy = NOSA_LAZY;   // the running max is only raised when it is exceeded by more than 2^kLazy
 
 struct PrefillArgs {
   const void* q;             // [B, Lq, Hq, d]
@@ -80,16 +84,15 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
   constexpr int RD = D / 32;    // 32-row tiles of O^T
   constexpr int kRowK = D * 2;  // bytes per row of the K tile
   constexpr int kRowV = 128;    // bytes per row of the V^T tile (64 keys)
-  constexpr int KR = kBlockTokens * CH / kThreads;         // 16-byte K loads per thread and tile
-  constexpr int VR = (kBlockTokens / 2) * CH / kThreads;   // key pairs of V per thread and tile
+  constexpr int kTile = 64 * kRowK + D * kRowV + 64 * 4;   // K tile, V^T tile, bias: one buffer
+  constexpr int KR = kBlockTokens * CH / kThreads;                 // 16-byte K loads per thread and tile (2 or 1)
+  constexpr int kPairs = (kBlockTokens / 2) * CH;                  // (key pair, chunk) tasks of the V tile: 512 or 256
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* Ks = smem;                                   // [64 keys][D] swizzled
-  unsigned char* Vt = Ks + 64 * kRowK;                        // [D][64 key positions] swizzled
-  float* bias_s = (float*)(Vt + D * kRowV);                   // [64], already times log2(e)
-  int* n_list_s = (int*)(bias_s + 64);                        // [4] (one used)
-  uint32_t* memb = (uint32_t*)(n_list_s + 4);                 // [list_cap] bit t: position t selected the block
-  int* list_j = (int*)(memb + a.list_cap);                    // [list_cap] visited blocks, ascending
-  uint32_t* list_m = (uint32_t*)(list_j + a.list_cap);        // [list_cap] their membership words
+  // two tile buffers, then the lists
+  int* n_list_s = (int*)(smem + 2 * kTile);                       // [4] (one used)
+  unsigned long long* memb = (unsigned long long*)(n_list_s + 4); // [list_cap] bit t: position t selected the block
+  unsigned long long* list_m = memb + a.list_cap;                 // [list_cap] membership words of the visited blocks
+  int* list_j = (int*)(list_m + a.list_cap);                      // [list_cap] visited blocks, ascending
 
   // workgroup -> (unit, query tile, head quad): id % 8 is the XCD the hardware dispatches to
   const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
@@ -98,17 +101,18 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
   if (unit >= a.units) return;                                 // before any barrier
   const int b = unit / a.n_kv_heads, h = unit % a.n_kv_heads;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-  const int g = hz * kHeadsPerWg + wave;
+  const int g = hz * kHeadsPerWg + (wave & 3);
+  const int ct = wave >> 2;             // which half of the 64 positions
   const bool active = g < a.group;      // wave-uniform
   const int hq = h * a.group + (active ? g : 0);
   const int l32 = lane % 32, hb = lane / 32;
   const int t0 = qt * kQ;                              // first chunk position of this tile
+  const int tq = ct * 32 + l32;                        // this lane's position in the tile = its row in the diagonal block
   const int diag = (a.p0 + t0) / kBlockTokens;         // the block these positions live in
-  const int toff = (a.p0 + t0) % kBlockTokens + l32;   // this lane's query, as a row of that block
   const int nblk = diag + 1;
   const float scale2 = a.scale * kLog2e;
 
-  for (int J = tid; J < nblk; J += kThreads) memb[J] = 0u;
+  for (int J = tid; J < nblk; J += kThreads) memb[J] = 0ull;
   __syncthreads();
   {
     const int K = a.k_blocks;
@@ -117,15 +121,15 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
       const size_t vu = ((size_t)b * a.lq + t0 + t) * a.n_kv_heads + h;
       if (k < a.n_sel[vu]) {
         const int J = a.sel_idx[vu * K + k];
-        if (J >= 0 && J < nblk) atomicOr(&memb[J], 1u << t);
+        if (J >= 0 && J < nblk) atomicOr(&memb[J], 1ull << t);
       }
     }
   }
 
-  // Q^T operand, resident for the whole kernel: lane = (query l32, k half hb)
+  // Q^T operand, resident for the whole kernel: lane = (query l32 of this wave's half, k half hb)
   bf16x8 qreg[KC];
   {
-    const size_t row = ((size_t)b * a.lq + t0 + l32) * a.n_q_heads + hq;
+    const size_t row = ((size_t)b * a.lq + t0 + tq) * a.n_q_heads + hq;
     const u32x4* qp = (const u32x4*)((const char*)a.q + row * (size_t)(D * 2));
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) qreg[kc] = __builtin_bit_cast(bf16x8, qp[2 * kc + hb]);
@@ -135,9 +139,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
     int n = 0;
     for (int base = 0; base < nblk; base += kWave) {
       const int J = base + lane;
-      const uint32_t m = J < nblk ? memb[J] : 0u;
-      const uint64_t bal = __ballot(m != 0u);
-      if (m != 0u) {
+      const unsigned long long m = J < nblk ? memb[J] : 0ull;
+      const uint64_t bal = __ballot(m != 0ull);
+      if (m != 0ull) {
         const int pos = n + (int)__popcll(bal & ((1ull << lane) - 1ull));
         list_j[pos] = J;
         list_m[pos] = m;
@@ -154,11 +158,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
   for (int rd = 0; rd < RD; ++rd)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[rd][i] = 0.f;
-  float m_run = -INFINITY;   // running max, in log2 units
+  float m_run = -INFINITY;   // reference max of the running sums, in log2 units
   float l_run = 0.f;         // this lane's share of the running sum
 
   const size_t unit_blk = (size_t)unit * a.max_blocks;
-  u32x4 kpre[KR], vpre0[VR], vpre1[VR];
+  u32x4 kpre[KR], vpre0, vpre1;
   float bpre = 0.f;
   auto fetch_tile = [&](int J) {   // global -> registers
     const size_t blk = unit_blk + J;
@@ -166,31 +170,30 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
     const char* vg = (const char*)a.cache_v + blk * (size_t)(kBlockTokens * kRowK);
 #pragma unroll
     for (int r = 0; r < KR; ++r) kpre[r] = *(const u32x4*)(kg + (size_t)(tid + r * kThreads) * 16);
-#pragma unroll
-    for (int r = 0; r < VR; ++r) {
-      const int i = tid + r * kThreads;
-      const int key = 2 * (i / CH), e = i % CH;
-      vpre0[r] = *(const u32x4*)(vg + ((size_t)key * CH + e) * 16);
-      vpre1[r] = *(const u32x4*)(vg + ((size_t)(key + 1) * CH + e) * 16);
+    if (tid < kPairs) {
+      const int key = 2 * (tid / CH), e = tid % CH;
+      vpre0 = *(const u32x4*)(vg + ((size_t)key * CH + e) * 16);
+      vpre1 = *(const u32x4*)(vg + ((size_t)(key + 1) * CH + e) * 16);
     }
     if (tid < kBlockTokens) bpre = a.cache_bias[blk * kBlockTokens + tid];
   };
-  auto stage_tile = [&]() {        // registers -> LDS (K swizzled, V transposed and swizzled)
+  auto stage_tile = [&](unsigned char* buf) {   // registers -> LDS (K swizzled, V transposed and swizzled)
+    unsigned char* Ks = buf;
+    unsigned char* Vt = buf + 64 * kRowK;
+    float* bias_s = (float*)(Vt + D * kRowV);
 #pragma unroll
     for (int r = 0; r < KR; ++r) {
       const int i = tid + r * kThreads;
       const int key = i / CH, c = i % CH;
       *(u32x4*)(Ks + key * kRowK + ((c ^ (key & 7)) * 16)) = kpre[r];
     }
-#pragma unroll
-    for (int r = 0; r < VR; ++r) {
-      const int i = tid + r * kThreads;
-      const int key = 2 * (i / CH), e = i % CH;
+    if (tid < kPairs) {
+      const int key = 2 * (tid / CH), e = tid % CH;
       const int pos = (key & ~0xC) | ((key & 8) >> 1) | ((key & 4) << 1);   // even; key + 1 sits at pos + 1
       const int chunk = (pos >> 3) ^ (e & 7);
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const uint32_t a0 = vpre0[r][w], a1 = vpre1[r][w];
+        const uint32_t a0 = vpre0[w], a1 = vpre1[w];
         const int dd = 8 * e + 2 * w;
         *(uint32_t*)(Vt + dd * kRowV + ((chunk ^ (dd & 7)) * 16) + (pos & 7) * 2) = (a0 & 0xffffu) | (a1 << 16);
         *(uint32_t*)(Vt + (dd + 1) * kRowV + ((chunk ^ ((dd + 1) & 7)) * 16) + (pos & 7) * 2) =
@@ -200,16 +203,23 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
     if (tid < kBlockTokens) bias_s[tid] = bpre * kLog2e;
   };
 
-  if (n_list > 0) fetch_tile(list_j[0]);
+  // tile it is multiplied out of buffer it & 1 while tile it + 1 is written into the other buffer
+  // and tile it + 2 travels from global memory into registers: one barrier per tile
+  if (n_list > 0) {
+    fetch_tile(list_j[0]);
+    stage_tile(smem);
+    if (n_list > 1) fetch_tile(list_j[1]);
+  }
+  __syncthreads();
   for (int it = 0; it < n_list; ++it) {
     const int J = list_j[it];
-    const uint32_t mb = list_m[it];
-    stage_tile();
-    __syncthreads();
-    if (it + 1 < n_list) fetch_tile(list_j[it + 1]);   // in flight during the arithmetic below
+    const unsigned long long mb = list_m[it];
+    const unsigned char* Ks = smem + (it & 1) * kTile;
+    const unsigned char* Vt = Ks + 64 * kRowK;
+    const float* bias_s = (const float*)(Vt + D * kRowV);
 
+    f32x16 s[2];   // two tiles of 32 keys
     if (active) {
-      f32x16 s[2];   // two tiles of 32 keys
 #pragma unroll
       for (int rk = 0; rk < 2; ++rk)
 #pragma unroll
@@ -223,7 +233,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
           s[rk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qreg[kc], s[rk], 0, 0, 0);
         }
       }
+    }
 
+    if (it + 1 < n_list) {
+      stage_tile(smem + ((it + 1) & 1) * kTile);
+      if (it + 2 < n_list) fetch_tile(list_j[it + 2]);
+    }
+
+    if (active) {
       // accumulator i of key tile rk is key rk*32 + 8*(i/4) + 4*hb + i%4
 #pragma unroll
       for (int rk = 0; rk < 2; ++rk)
@@ -240,9 +257,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
         for (int rk = 0; rk < 2; ++rk)
 #pragma unroll
           for (int i = 0; i < 16; ++i)
-            if (rk * 32 + 8 * (i / 4) + 4 * hb + (i % 4) > toff) s[rk][i] = -INFINITY;
+            if (rk * 32 + 8 * (i / 4) + 4 * hb + (i % 4) > tq) s[rk][i] = -INFINITY;
       }
-      const bool member = (mb >> l32) & 1u;
+      const bool member = (mb >> tq) & 1ull;
       float mx = -INFINITY;
 #pragma unroll
       for (int rk = 0; rk < 2; ++rk)
@@ -250,10 +267,22 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[rk][i]);
       if (!member) mx = -INFINITY;
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx);
+      // The reference max only moves when it is exceeded by more than 2^kLazy: the sums stay within
+      // fp32 range (terms < 2^kLazy), the quotient o / l is unchanged, and the accumulators are
+      // rescaled a handful of times per row instead of at every new maximum.
+      const bool raise = mx > m_run + kLazy || (m_run == -INFINITY && mx != -INFINITY);
+      if (__any(raise)) {
+        const float m_new = raise ? mx : m_run;
+        const float alpha = (raise && m_run != -INFINITY) ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
+        l_run *= alpha;
+        m_run = m_new;
+#pragma unroll
+        for (int rd = 0; rd < RD; ++rd)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[rd][i] *= alpha;
+      }
       // positions outside the block's membership, and ones that have seen nothing yet, add zeros
-      const float sub = (member && m_new != -INFINITY) ? m_new : INFINITY;
-      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
+      const float sub = (member && m_run != -INFINITY) ? m_run : INFINITY;
       float psum = 0.f;
       uint32_t packed[16];
 #pragma unroll
@@ -266,14 +295,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
           packed[rk * 8 + i / 2] = pack_bf16(p0, p1);
         }
       }
-      l_run = l_run * alpha + psum;
-      m_run = m_new;
-      if (__any(alpha != 1.f)) {
-#pragma unroll
-        for (int rd = 0; rd < RD; ++rd)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) o[rd][i] *= alpha;
-      }
+      l_run += psum;
 #pragma unroll
       for (int kc = 0; kc < 4; ++kc) {
         const u32x4 w = {packed[4 * kc], packed[4 * kc + 1], packed[4 * kc + 2], packed[4 * kc + 3]};
@@ -287,14 +309,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
         }
       }
     }
-    __syncthreads();   // the tile has been consumed
+    __syncthreads();   // tile it has been consumed, tile it + 1 is in place
   }
 
   if (active) {
     float l = l_run;
     l += __shfl_xor(l, 32);
     const float inv = l > 0.f ? 1.f / l : 0.f;
-    const size_t row = ((size_t)b * a.lq + t0 + l32) * a.n_q_heads + hq;
+    const size_t row = ((size_t)b * a.lq + t0 + tq) * a.n_q_heads + hq;
     char* op = (char*)a.out + row * (size_t)(D * 2);
 #pragma unroll
     for (int rd = 0; rd < RD; ++rd) {
@@ -311,7 +333,6 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
   }
 }
 
-
 // Block scores of a whole chunk as one matrix product per (batch element, KV head), for one pooled
 // key per block (Alg. 1 Stage 1 with pool kernel = stride = block size): sq[t, J] = sum over the G
 // query heads of q_{t,g} . kc_J.  The group sum is folded into the contraction (k runs over g and
@@ -327,8 +348,10 @@ struct PrefillScoreArgs {
   int n_kv_heads, group, n_q_heads, max_blocks, n_sub_max, p0, lq;
 };
 
+constexpr int kScoreThreads = 256;
+
 template <int D>
-__global__ __launch_bounds__(kThreads) void prefill_score_kernel(const PrefillScoreArgs a) {
+__global__ __launch_bounds__(kScoreThreads) void prefill_score_kernel(const PrefillScoreArgs a) {
   constexpr int CH = D / 8, KC = D / 16, kRow = D * 2;
   extern __shared__ __align__(16) unsigned char smem[];   // [G][32 positions][D] swizzled
   const int tt = blockIdx.x, unit = blockIdx.y;
@@ -340,7 +363,7 @@ __global__ __launch_bounds__(kThreads) void prefill_score_kernel(const PrefillSc
   if ((int)blockIdx.z * 512 >= n_hi) return;                            // whole workgroup: nothing to score
 
   const int rows = a.group * 32;
-  for (int i = tid; i < rows * CH; i += kThreads) {
+  for (int i = tid; i < rows * CH; i += kScoreThreads) {
     const int r = i / CH, c = i % CH;          // r = g * 32 + position
     const int g = r / 32, tl = r % 32;
     const size_t row = ((size_t)b * a.lq + t0 + tl) * a.n_q_heads + h * a.group + g;
@@ -409,8 +432,8 @@ int launch_prefill_score(nosa_ctx* ctx, const void* q_chunk, const void* k_poole
   NOSA_REQUIRE(ctx, smem <= 64 * 1024, NOSA_ESHAPE, "prefill: %d query heads per KV head need %zu bytes of LDS", ctx->group, smem);
   NOSA_REQUIRE(ctx, ctx->units <= 65535 && grid.z <= 65535, NOSA_ESHAPE, "prefill: B * Hkv = %d exceeds 65535", ctx->units);
   TimedLaunch tl(ctx, NOSA_KERNEL_SCORE, ctx->main);
-  if (p.head_dim == 128) hipLaunchKernelGGL(prefill_score_kernel<128>, grid, dim3(kThreads), smem, ctx->main, a);
-  else hipLaunchKernelGGL(prefill_score_kernel<64>, grid, dim3(kThreads), smem, ctx->main, a);
+  if (p.head_dim == 128) hipLaunchKernelGGL(prefill_score_kernel<128>, grid, dim3(kScoreThreads), smem, ctx->main, a);
+  else hipLaunchKernelGGL(prefill_score_kernel<64>, grid, dim3(kScoreThreads), smem, ctx->main, a);
   NOSA_HIP(ctx, hipGetLastError());
   return NOSA_OK;
 }
@@ -423,10 +446,16 @@ int launch_prefill_attend(nosa_ctx* ctx, const void* q_chunk, const void* cache_
   const int list_cap = (p0 + lq) / kBlockTokens;
   PrefillArgs a{q_chunk, cache_k, cache_v, cache_bias, sel_idx, n_sel, out, lse, p.n_kv_heads, ctx->group,
                 p.n_q_heads, p.max_blocks, p.k_blocks, p0, lq, ctx->units, n_qt, n_hz, list_cap, ctx->scale};
-  const size_t smem = (size_t)kBlockTokens * p.head_dim * 2 + (size_t)p.head_dim * 128 + 64 * sizeof(float) + 16 +
-                      (size_t)list_cap * 12;
-  NOSA_REQUIRE(ctx, smem <= 64 * 1024, NOSA_ESHAPE, "prefill: %d blocks of context need %zu bytes of LDS (limit 65536)",
+  const size_t tile = (size_t)kBlockTokens * p.head_dim * 2 + (size_t)p.head_dim * 128 + 64 * sizeof(float);
+  const size_t smem = 2 * tile + 16 + (size_t)list_cap * 20;
+  NOSA_REQUIRE(ctx, smem <= 160 * 1024, NOSA_ESHAPE, "prefill: %d blocks of context need %zu bytes of LDS (limit 163840)",
                list_cap, smem);
+  if (smem > 64 * 1024) {
+    if (p.head_dim == 128)
+      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_attend_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    else
+      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_attend_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+  }
   const long long wgs = (long long)kXcds * ((ctx->units + kXcds - 1) / kXcds) * n_qt * n_hz;
   NOSA_REQUIRE(ctx, wgs <= 0x7fffffffLL, NOSA_ESHAPE, "prefill: too many workgroups (%lld)", wgs);
   const dim3 grid((unsigned)wgs);

@@ -40,8 +40,9 @@ __device__ __forceinline__ int take_top(uint32_t (&keys)[R], uint32_t (&other)[R
 #pragma unroll
       for (int r = 0; r < R; ++r) cnt += (int)__popcll(__ballot(keys[r] >= cand));
       if (cnt >= want) prefix = cand;
+      if (cnt == want) break;   // exactly the keys >= cand win: the threshold's lower bits do not matter
     }
-    thr = prefix;   // the want-th largest key
+    thr = prefix;   // the want-th largest key, or a bound with exactly `want` keys at or above it
   } else {
     want = n_eligible;
   }
