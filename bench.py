@@ -280,12 +280,12 @@ def prefill_study(args):
     caches, qs = [], []
     n_full = torch.full((B,), w.context, dtype=torch.int32, device=dev)
     for l in range(L):
-        lay = make_layer(w, args.seed, l, device=dev)
+        lay = {k: v.to(dev) for k, v in make_layer(w, args.seed, l).items() if k.startswith("host_")}
         kc = torch.zeros((B, H, w.n_sub_max, d), dtype=td, device=dev)
         sec = torch.zeros((B, H, w.n_sub_max), dtype=torch.float32, device=dev)
         ctx.nosa_pool_blocks(lay["host_k"], lay["host_bias"], n_full, kc, sec)
         caches.append((lay["host_k"], lay["host_v"], lay["host_bias"], kc, sec))
-        qs.append(chunk_queries(w, args.seed, l, lq, device=dev).to(td))
+        qs.append(chunk_queries(w, args.seed, l, lq).to(td).to(dev))
     n_tok_s = torch.empty((B * lq,), dtype=torch.int32, device=dev)
     sq_s = torch.empty((B, lq, H, w.max_blocks), dtype=torch.float32, device=dev)
     se_s = torch.empty_like(sq_s)

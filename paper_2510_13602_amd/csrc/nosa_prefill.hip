@@ -47,11 +47,6 @@ constexpr int kQ = 64;            // query positions per workgroup
 constexpr int kHeadsPerWg = 4;    // two waves each (32 positions per wave)
 constexpr int kXcds = 8;
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-#ifndef NOSA_LAZY
-#define NOSA_LAZY 0.f
-#endif
-constexpr float kLazy = NOSA_LAZY;   // the running max is only raised when it is exceeded by more than 2^kLazy
 
 struct PrefillArgs {
   const void* q;             // [B, Lq, Hq, d]
@@ -87,6 +82,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
   constexpr int kTile = 64 * kRowK + D * kRowV + 64 * 4;   // K tile, V^T tile, bias: one buffer
   constexpr int KR = kBlockTokens * CH / kThreads;                 // 16-byte K loads per thread and tile (2 or 1)
   constexpr int kPairs = (kBlockTokens / 2) * CH;                  // (key pair, chunk) tasks of the V tile: 512 or 256
+  // 16-byte chunk c of key row `key` sits at chunk c ^ kswz(key): the rows that one operand read touches
+  // (16 neighbouring keys at a time) then fall into 16 different 16-byte bank groups (256 bytes per clock)
+  auto kswz = [](int key) { return D == 128 ? (key & 15) : ((key >> 1) & 7); };
   extern __shared__ __align__(16) unsigned char smem[];
   // two tile buffers, then the lists
   int* n_list_s = (int*)(smem + 2 * kTile);                       // [4] (one used)
@@ -110,7 +108,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
   const int tq = ct * 32 + l32;                        // this lane's position in the tile = its row in the diagonal block
   const int diag = (a.p0 + t0) / kBlockTokens;         // the block these positions live in
   const int nblk = diag + 1;
-  const float scale2 = a.scale * kLog2e;
+  const float scale2 = a.scale * kLog2e;      // logits are kept unscaled; 2^(scale2 * x) = e^(scale * x)
+  const float inv_scale = 1.f / a.scale;
 
   for (int J = tid; J < nblk; J += kThreads) memb[J] = 0ull;
   __syncthreads();
@@ -158,7 +157,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
   for (int rd = 0; rd < RD; ++rd)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[rd][i] = 0.f;
-  float m_run = -INFINITY;   // reference max of the running sums, in log2 units
+  float m_run = -INFINITY;   // running max of the unscaled logits q.k + bias / scale
   float l_run = 0.f;         // this lane's share of the running sum
 
   const size_t unit_blk = (size_t)unit * a.max_blocks;
@@ -180,12 +179,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
   auto stage_tile = [&](unsigned char* buf) {   // registers -> LDS (K swizzled, V transposed and swizzled)
     unsigned char* Ks = buf;
     unsigned char* Vt = buf + 64 * kRowK;
-    float* bias_s = (float*)(Vt + D * kRowV);
+    float* bias_s = (float*)(Vt + D * kRowV);   // [64] bias / scale
 #pragma unroll
     for (int r = 0; r < KR; ++r) {
       const int i = tid + r * kThreads;
       const int key = i / CH, c = i % CH;
-      *(u32x4*)(Ks + key * kRowK + ((c ^ (key & 7)) * 16)) = kpre[r];
+      *(u32x4*)(Ks + key * kRowK + ((c ^ kswz(key)) * 16)) = kpre[r];
     }
     if (tid < kPairs) {
       const int key = 2 * (tid / CH), e = tid % CH;
@@ -200,7 +199,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
             (a0 >> 16) | (a1 & 0xffff0000u);
       }
     }
-    if (tid < kBlockTokens) bias_s[tid] = bpre * kLog2e;
+    if (tid < kBlockTokens) bias_s[tid] = bpre * inv_scale;
   };
 
   // tile it is multiplied out of buffer it & 1 while tile it + 1 is written into the other buffer
@@ -220,16 +219,24 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
 
     f32x16 s[2];   // two tiles of 32 keys
     if (active) {
+      // accumulator i of key tile rk is key rk*32 + 8*(i/4) + 4*hb + i%4; it starts at that key's
+      // bias / scale, so that scale * S is the biased logit without a separate addition
 #pragma unroll
       for (int rk = 0; rk < 2; ++rk)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[rk][i] = 0.f;
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const float4 bz = *(const float4*)(bias_s + rk * 32 + 8 * i4 + 4 * hb);
+          s[rk][4 * i4 + 0] = bz.x;
+          s[rk][4 * i4 + 1] = bz.y;
+          s[rk][4 * i4 + 2] = bz.z;
+          s[rk][4 * i4 + 3] = bz.w;
+        }
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) {
 #pragma unroll
         for (int rk = 0; rk < 2; ++rk) {
           const int key = rk * 32 + l32;
-          const bf16x8 ak = *(const bf16x8*)(Ks + key * kRowK + (((2 * kc + hb) ^ (key & 7)) * 16));
+          const bf16x8 ak = *(const bf16x8*)(Ks + key * kRowK + (((2 * kc + hb) ^ kswz(key)) * 16));
           s[rk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qreg[kc], s[rk], 0, 0, 0);
         }
       }
@@ -241,17 +248,6 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
     }
 
     if (active) {
-      // accumulator i of key tile rk is key rk*32 + 8*(i/4) + 4*hb + i%4
-#pragma unroll
-      for (int rk = 0; rk < 2; ++rk)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const float4 bz = *(const float4*)(bias_s + rk * 32 + 8 * i4 + 4 * hb);
-          s[rk][4 * i4 + 0] = fmaf(s[rk][4 * i4 + 0], scale2, bz.x);
-          s[rk][4 * i4 + 1] = fmaf(s[rk][4 * i4 + 1], scale2, bz.y);
-          s[rk][4 * i4 + 2] = fmaf(s[rk][4 * i4 + 2], scale2, bz.z);
-          s[rk][4 * i4 + 3] = fmaf(s[rk][4 * i4 + 3], scale2, bz.w);
-        }
       if (J == diag) {   // the future
 #pragma unroll
         for (int rk = 0; rk < 2; ++rk)
@@ -267,30 +263,27 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[rk][i]);
       if (!member) mx = -INFINITY;
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      // The reference max only moves when it is exceeded by more than 2^kLazy: the sums stay within
-      // fp32 range (terms < 2^kLazy), the quotient o / l is unchanged, and the accumulators are
-      // rescaled a handful of times per row instead of at every new maximum.
-      const bool raise = mx > m_run + kLazy || (m_run == -INFINITY && mx != -INFINITY);
+      const bool raise = mx > m_run;
       if (__any(raise)) {
-        const float m_new = raise ? mx : m_run;
-        const float alpha = (raise && m_run != -INFINITY) ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
+        const float alpha = (raise && m_run != -INFINITY) ? __builtin_amdgcn_exp2f((m_run - mx) * scale2) : 1.f;
+        if (raise) m_run = mx;
         l_run *= alpha;
-        m_run = m_new;
 #pragma unroll
         for (int rd = 0; rd < RD; ++rd)
 #pragma unroll
           for (int i = 0; i < 16; ++i) o[rd][i] *= alpha;
       }
-      // positions outside the block's membership, and ones that have seen nothing yet, add zeros
-      const float sub = (member && m_run != -INFINITY) ? m_run : INFINITY;
+      // p = 2^(scale2 * (S - m)); positions outside the block's membership, and ones that have seen
+      // nothing yet, add zeros
+      const float off = (member && m_run != -INFINITY) ? -m_run * scale2 : -INFINITY;
       float psum = 0.f;
       uint32_t packed[16];
 #pragma unroll
       for (int rk = 0; rk < 2; ++rk) {
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(s[rk][i] - sub);
-          const float p1 = __builtin_amdgcn_exp2f(s[rk][i + 1] - sub);
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[rk][i], scale2, off));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[rk][i + 1], scale2, off));
           psum += p0 + p1;
           packed[rk * 8 + i / 2] = pack_bf16(p0, p1);
         }
@@ -329,7 +322,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
         *(uint2*)(op + dd * 2) = w;
       }
     }
-    if (hb == 0) a.lse[row] = l > 0.f ? m_run * kLn2 + logf(l) : -INFINITY;
+    if (hb == 0) a.lse[row] = l > 0.f ? m_run * a.scale + logf(l) : -INFINITY;
   }
 }
 
