@@ -321,8 +321,8 @@ def prefill_study(args):
     t_in_blk = (torch.arange(lq, device=dev) % 64).view(1, lq, 1)
     tokens = (n_sel.long() * 64 - (63 - t_in_blk)).sum().item()
     flops = 4.0 * d * w.group * tokens
-    s4 = sel.view(B, lq // 32, 32, H, K).permute(0, 1, 3, 2, 4).reshape(B, lq // 32, H, 32 * K).long()
-    member = torch.zeros((B, lq // 32, H, w.max_blocks + 1), dtype=torch.bool, device=dev)
+    s4 = sel.view(B, lq // 64, 64, H, K).permute(0, 1, 3, 2, 4).reshape(B, lq // 64, H, 64 * K).long()
+    member = torch.zeros((B, lq // 64, H, w.max_blocks + 1), dtype=torch.bool, device=dev)
     member.scatter_(3, torch.where(s4 >= 0, s4, torch.full_like(s4, w.max_blocks)), True)
     union = member[..., :w.max_blocks].sum(-1).float()
     t_att = kern["prefill_attend"] * 1e-6
