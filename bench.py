@@ -7,7 +7,10 @@ layer of the 8B-shaped workload (batch 64, 32 query / 8 KV heads, d 128, 32768 t
 K = 64 blocks, fetch budget Kq = 8, bf16).  Successive steps cycle through distinct layers, so no
 step finds its KV pool in cache.  The metric counts (batch x KV head x layer) units per second.
 
-Prints ONE JSON line; see the design doc for the meaning of every field.
+Prints ONE JSON line.  `value` counts units per second over the timed steps (inputs resident before the
+timed region); `roofline` prices the attention kernel's algorithmic HBM bytes per launch, timed with HIP
+events inside the same region, against the 8 TB/s peak; `cpu_baseline` is the fp64 CPU oracle on a bounded
+sample of the same tensors.  `--study prefill` and `--study transfer` print lines of their own.
 """
 from __future__ import annotations
 
