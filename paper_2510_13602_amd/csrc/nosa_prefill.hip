@@ -422,7 +422,14 @@ int launch_prefill_score(nosa_ctx* ctx, const void* q_chunk, const void* k_poole
   const int n_hi = (p0 + lq) / kBlockTokens;
   const dim3 grid(lq / 32, ctx->units, (n_hi + 511) / 512);
   const size_t smem = (size_t)ctx->group * 32 * p.head_dim * 2;
-  NOSA_REQUIRE(ctx, smem <= 64 * 1024, NOSA_ESHAPE, "prefill: %d query heads per KV head need %zu bytes of LDS", ctx->group, smem);
+  NOSA_REQUIRE(ctx, smem <= 160 * 1024, NOSA_ESHAPE, "prefill: %d query heads per KV head need %zu bytes of LDS (limit 163840)",
+               ctx->group, smem);
+  if (smem > 64 * 1024) {
+    if (p.head_dim == 128)
+      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_score_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    else
+      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_score_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+  }
   NOSA_REQUIRE(ctx, ctx->units <= 65535 && grid.z <= 65535, NOSA_ESHAPE, "prefill: B * Hkv = %d exceeds 65535", ctx->units);
   TimedLaunch tl(ctx, NOSA_KERNEL_SCORE, ctx->main);
   if (p.head_dim == 128) hipLaunchKernelGGL(prefill_score_kernel<128>, grid, dim3(kScoreThreads), smem, ctx->main, a);

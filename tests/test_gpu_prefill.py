@@ -2,7 +2,7 @@
 oracle.prefill: the selection of every query position bit-exact, attention outputs within the
 bf16 bar (max abs 1e-2), log-sum-exp within 1e-2.
 
-Shapes cover both head dims, groups of 2 / 4 / 6 / 8 query heads per KV head (fewer, exactly and
+Shapes cover both head dims, groups of 2 / 4 / 6 / 8 / 16 query heads per KV head (fewer, exactly and
 more than the four waves of a workgroup), chunks that start at position 0 (positions with fewer
 blocks than the budget), chunks deep in a context, one and several 64-position workgroups, and the
 8B-shaped case at full size on sampled positions.
@@ -26,6 +26,7 @@ pytestmark = pytest.mark.gpu
     ("d128_g4_one_wg", dict(batch=1, n_q_heads=4, n_kv_heads=1, head_dim=128, k_blocks=5, kq_blocks=1, window_blocks=1), 64 * 9, 64),
     ("overlapping_pool_windows", dict(n_q_heads=8, n_kv_heads=2, head_dim=128, k_blocks=8, kq_blocks=2, window_blocks=2,
                                       pool_kernel=32, pool_stride=16), 64 * 6, 64 * 4),
+    ("d128_g16", dict(n_q_heads=16, n_kv_heads=1, head_dim=128, k_blocks=7, kq_blocks=2, window_blocks=2), 64 * 7, 64 * 2),
     ("budget_covers_all", dict(n_q_heads=8, n_kv_heads=2, head_dim=128, k_blocks=10, kq_blocks=4, window_blocks=2), 0, 64 * 8),
 ])
 def test_prefill_parity(name, kw, p0, lq):
