@@ -217,8 +217,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
     const unsigned char* Vt = Ks + 64 * kRowK;
     const float* bias_s = (const float*)(Vt + D * kRowV);
 
+    // a wave whose 32 positions all left this block out only helps with the staging
+    const bool busy = active && ((mb >> (ct * 32)) & 0xffffffffull) != 0ull;
     f32x16 s[2];   // two tiles of 32 keys
-    if (active) {
+    if (busy) {
       // accumulator i of key tile rk is key rk*32 + 8*(i/4) + 4*hb + i%4; it starts at that key's
       // bias / scale, so that scale * S is the biased logit without a separate addition
 #pragma unroll
@@ -247,7 +249,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
       if (it + 2 < n_list) fetch_tile(list_j[it + 2]);
     }
 
-    if (active) {
+    if (busy) {
       if (J == diag) {   // the future
 #pragma unroll
         for (int rk = 0; rk < 2; ++rk)
