@@ -29,6 +29,7 @@
 // neighbouring query tiles of the same (batch element, KV head): they share most of their
 // blocks (the query-agnostic picks and overlapping windows), which then come from that XCD's L2.
 #include <cmath>
+#include <type_traits>
 
 #include "nosa_device.h"
 #include "nosa_internal.h"
@@ -70,6 +71,17 @@ __global__ void prefill_positions_kernel(int32_t* n_tok, int p0, int lq, int tot
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // round to nearest even (v_cvt_pk_bf16_f32)
   const f32x2 v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// Lanes i and i + 32 hold the two halves of one query's keys: v_permlane32_swap exchanges the upper half
+// of one operand with the lower half of the other (no LDS round trip as with a shuffle).
+__device__ __forceinline__ float pair_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 template <int D>
@@ -161,22 +173,23 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
   float l_run = 0.f;         // this lane's share of the running sum
 
   const size_t unit_blk = (size_t)unit * a.max_blocks;
-  u32x4 kpre[KR], vpre0, vpre1;
-  float bpre = 0.f;
-  auto fetch_tile = [&](int J) {   // global -> registers
+  // two tiles travel from global memory through registers at any time (tile j uses set j & 1)
+  struct Pre { u32x4 k[KR], v0, v1; float b; } pre[2];
+  pre[0].b = pre[1].b = 0.f;
+  auto fetch_tile = [&](int J, Pre& R) {   // global -> registers
     const size_t blk = unit_blk + J;
     const char* kg = (const char*)a.cache_k + blk * (size_t)(kBlockTokens * kRowK);
     const char* vg = (const char*)a.cache_v + blk * (size_t)(kBlockTokens * kRowK);
 #pragma unroll
-    for (int r = 0; r < KR; ++r) kpre[r] = *(const u32x4*)(kg + (size_t)(tid + r * kThreads) * 16);
+    for (int r = 0; r < KR; ++r) R.k[r] = *(const u32x4*)(kg + (size_t)(tid + r * kThreads) * 16);
     if (tid < kPairs) {
       const int key = 2 * (tid / CH), e = tid % CH;
-      vpre0 = *(const u32x4*)(vg + ((size_t)key * CH + e) * 16);
-      vpre1 = *(const u32x4*)(vg + ((size_t)(key + 1) * CH + e) * 16);
+      R.v0 = *(const u32x4*)(vg + ((size_t)key * CH + e) * 16);
+      R.v1 = *(const u32x4*)(vg + ((size_t)(key + 1) * CH + e) * 16);
     }
-    if (tid < kBlockTokens) bpre = a.cache_bias[blk * kBlockTokens + tid];
+    if (tid < kBlockTokens) R.b = a.cache_bias[blk * kBlockTokens + tid];
   };
-  auto stage_tile = [&](unsigned char* buf) {   // registers -> LDS (K swizzled, V transposed and swizzled)
+  auto stage_tile = [&](unsigned char* buf, const Pre& R) {   // registers -> LDS (K swizzled, V transposed and swizzled)
     unsigned char* Ks = buf;
     unsigned char* Vt = buf + 64 * kRowK;
     float* bias_s = (float*)(Vt + D * kRowV);   // [64] bias / scale
@@ -184,7 +197,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
     for (int r = 0; r < KR; ++r) {
       const int i = tid + r * kThreads;
       const int key = i / CH, c = i % CH;
-      *(u32x4*)(Ks + key * kRowK + ((c ^ kswz(key)) * 16)) = kpre[r];
+      *(u32x4*)(Ks + key * kRowK + ((c ^ kswz(key)) * 16)) = R.k[r];
     }
     if (tid < kPairs) {
       const int key = 2 * (tid / CH), e = tid % CH;
@@ -192,28 +205,40 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
       const int chunk = (pos >> 3) ^ (e & 7);
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const uint32_t a0 = vpre0[w], a1 = vpre1[w];
+        const uint32_t a0 = R.v0[w], a1 = R.v1[w];
         const int dd = 8 * e + 2 * w;
         *(uint32_t*)(Vt + dd * kRowV + ((chunk ^ (dd & 7)) * 16) + (pos & 7) * 2) = (a0 & 0xffffu) | (a1 << 16);
         *(uint32_t*)(Vt + (dd + 1) * kRowV + ((chunk ^ ((dd + 1) & 7)) * 16) + (pos & 7) * 2) =
             (a0 >> 16) | (a1 & 0xffff0000u);
       }
     }
-    if (tid < kBlockTokens) bias_s[tid] = bpre * inv_scale;
+    if (tid < kBlockTokens) bias_s[tid] = R.b * inv_scale;
   };
 
   // tile it is multiplied out of buffer it & 1 while tile it + 1 is written into the other buffer
-  // and tile it + 2 travels from global memory into registers: one barrier per tile
+  // and tiles it + 2, it + 3 travel from global memory into registers: one barrier per tile
+  int J_next = 0;
+  unsigned long long mb_next = 0ull;
   if (n_list > 0) {
-    fetch_tile(list_j[0]);
-    stage_tile(smem);
-    if (n_list > 1) fetch_tile(list_j[1]);
+    fetch_tile(list_j[0], pre[0]);
+    stage_tile(smem, pre[0]);
+    if (n_list > 1) fetch_tile(list_j[1], pre[1]);
+    if (n_list > 2) fetch_tile(list_j[2], pre[0]);
+    J_next = list_j[0];
+    mb_next = list_m[0];
   }
   __syncthreads();
-  for (int it = 0; it < n_list; ++it) {
-    const int J = list_j[it];
-    const unsigned long long mb = list_m[it];
-    const unsigned char* Ks = smem + (it & 1) * kTile;
+  // one visited block; PAR = it & 1 is a compile-time constant so that the buffer offsets fold into the
+  // LDS instructions' immediate fields (the loop below is unrolled by two)
+  auto pass = [&](int it, auto par) {
+    constexpr int PAR = decltype(par)::value;
+    const int J = J_next;                      // read one pass ahead: no LDS round trip at the top of a pass
+    const unsigned long long mb = mb_next;
+    if (it + 1 < n_list) {
+      J_next = list_j[it + 1];
+      mb_next = list_m[it + 1];
+    }
+    const unsigned char* Ks = smem + PAR * kTile;
     const unsigned char* Vt = Ks + 64 * kRowK;
     const float* bias_s = (const float*)(Vt + D * kRowV);
 
@@ -245,8 +270,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
     }
 
     if (it + 1 < n_list) {
-      stage_tile(smem + ((it + 1) & 1) * kTile);
-      if (it + 2 < n_list) fetch_tile(list_j[it + 2]);
+      stage_tile(smem + (PAR ^ 1) * kTile, pre[PAR ^ 1]);
+      if (it + 3 < n_list) fetch_tile(list_j[it + 3], pre[PAR ^ 1]);
     }
 
     if (busy) {
@@ -264,7 +289,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
 #pragma unroll
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[rk][i]);
       if (!member) mx = -INFINITY;
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      mx = pair_max(mx);
       const bool raise = mx > m_run;
       if (__any(raise)) {
         const float alpha = (raise && m_run != -INFINITY) ? __builtin_amdgcn_exp2f((m_run - mx) * scale2) : 1.f;
@@ -305,11 +330,15 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attend_kernel(const Prefi
       }
     }
     __syncthreads();   // tile it has been consumed, tile it + 1 is in place
+  };
+  for (int it = 0; it < n_list; it += 2) {
+    pass(it, std::integral_constant<int, 0>{});
+    if (it + 1 < n_list) pass(it + 1, std::integral_constant<int, 1>{});
   }
 
   if (active) {
     float l = l_run;
-    l += __shfl_xor(l, 32);
+    l = pair_sum(l);
     const float inv = l > 0.f ? 1.f / l : 0.f;
     const size_t row = ((size_t)b * a.lq + t0 + tq) * a.n_q_heads + hq;
     char* op = (char*)a.out + row * (size_t)(D * 2);
