@@ -72,6 +72,8 @@ def test_null_arguments_are_errors_not_crashes():
     assert lib.nosa_select(None, *([None] * 9)) == nosa.binding.NOSA_EINVAL
     assert lib.nosa_fetch(None, *([None] * 8)) == nosa.binding.NOSA_EINVAL
     assert lib.nosa_sparse_decode(None, *([None] * 10)) == nosa.binding.NOSA_EINVAL
+    assert lib.nosa_prefill_select(None, None, None, None, 0, 64, None, None, None, None, None) == nosa.binding.NOSA_EINVAL
+    assert lib.nosa_prefill_attend(None, None, None, None, None, None, None, 0, 64, None, None) == nosa.binding.NOSA_EINVAL
     assert b"NULL" in lib.nosa_last_error(None)
 
 
