@@ -47,6 +47,8 @@ def parse_args():
                          "prefill: sparse prefill of one chunk at the end of the 8B-shaped context (one JSON line)")
     ap.add_argument("--prefill-batch", type=int, default=4)
     ap.add_argument("--prefill-chunk", type=int, default=2048, help="query positions per chunk (multiple of 64)")
+    ap.add_argument("--prefill-all", action="store_true",
+                    help="prefill study: also time every chunk of the context from position 0 and report the whole-prompt rate")
     ap.add_argument("--mode", default="fused", choices=["calls", "fused", "graph"],
                     help="how a step crosses the C ABI: four calls, the single nosa_decode_step entry, or a HIP graph replay")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -342,6 +344,27 @@ def prefill_study(args):
         "kernels_avg_us": kern,
         "union_blocks_per_workgroup": {"mean": float(union.mean().item()), "max": float(union.max().item()), "budget": K},
     }
+    if args.prefill_all:
+        # the whole prompt, chunk by chunk (the cache already holds it; a chunk sees only its own prefix)
+        per_chunk = []
+        ck, cv, cb, kc, sec = caches[0]
+        q = qs[0]
+        for c0 in range(0, w.context, lq):
+            ctx.nosa_prefill_select(q, kc, sec, c0, lq, n_tok_s, sq_s, se_s, sel, n_sel)
+            ctx.nosa_prefill_attend(q, ck, cv, cb, sel, n_sel, c0, lq, out, lse)
+        torch.cuda.synchronize()
+        for c0 in range(0, w.context, lq):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(4):
+                ctx.nosa_prefill_select(q, kc, sec, c0, lq, n_tok_s, sq_s, se_s, sel, n_sel)
+                ctx.nosa_prefill_attend(q, ck, cv, cb, sel, n_sel, c0, lq, out, lse)
+            e1.record(stream)
+            e1.synchronize()
+            per_chunk.append(e0.elapsed_time(e1) / 4)
+        total_ms = sum(per_chunk)
+        line["whole_prompt"] = {"chunks": len(per_chunk), "ms_per_chunk": [round(x, 3) for x in per_chunk], "ms_per_layer": total_ms,
+                                "tokens_per_s_per_layer": B * w.context / (total_ms * 1e-3)}
     ctx.close()
     print(json.dumps(line), flush=True)
 
