@@ -232,7 +232,8 @@ int nosa_split_qkv_evict(nosa_ctx* ctx, const void* qkv, const float* w1, const 
  * has a slot, to that slot.  A token that opens a new block first gives the block a slot: the lowest
  * empty slot, else the slot of the resident block with the smallest se_blk (block-level importance
  * as written by the last nosa_block_score; ties: lower slot) among blocks that are neither sink
- * blocks nor among the last max(Nw, 2) blocks before J; if there is none the block stays
+ * blocks nor among the Nw - 1 blocks before J that stay in the window (the block that leaves the
+ * window, J - Nw, is a candidate like any other); if there is none the block stays
  * non-resident and the next nosa_select lists it as a miss.  Evicting the least important candidate
  * keeps the per-step fetch bound of Theorem 1 across block boundaries.  Then every sub-block that
  * this token completes gets its pooled key and pooled importance (same arithmetic as

@@ -429,7 +429,8 @@ int oracle_attention(const oracle_params *p, const void *q, const void *pool_k, 
  * element b is written to the host pool (block J = t / nb, row t % nb) and, if block J has a slot,
  * to that slot.  When the token opens a new block (row 0) the block is given a slot first: the lowest
  * empty slot, else the slot whose block has the smallest block-level importance se_blk among the
- * resident blocks that are neither sink blocks nor among the last max(Nw, 2) blocks before J (ties:
+ * resident blocks that are neither sink blocks nor among the Nw - 1 blocks before J that stay in the
+ * window (the block that leaves the window, J - Nw, is a candidate like any other) (ties:
  * lower slot); if there is none the block simply stays non-resident and is fetched like any miss.
  * Evicting the least important resident candidate keeps the Ke best-by-importance candidates
  * resident, which is what the proof of Theorem 1 needs for the per-step fetch bound.
@@ -457,7 +458,7 @@ void oracle_append(const oracle_params *p, const void *k_new, const void *v_new,
       int best = -1;
       for (int s = 0; s < C && best < 0; ++s) if (bos[s] < 0) best = s;
       if (best < 0) {
-        const int protect = p->window_blocks > 2 ? p->window_blocks : 2;
+        const int protect = p->window_blocks;   /* blocks J-Nw+1 .. J-1 stay in the window */
         for (int s = 0; s < C; ++s) {
           const int Jp = bos[s];
           if (Jp < p->sink_blocks || Jp > J - protect) continue;

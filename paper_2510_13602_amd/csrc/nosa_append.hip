@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kWave) void append_kernel(const AppendArgs a) {
   int slot = sob[J];
   if (row == 0 && slot < 0) {
     // lowest empty slot, else the least important resident candidate (ties: lower slot)
-    const int protect = a.window_blocks > 2 ? a.window_blocks : 2;
+    const int protect = a.window_blocks;   // blocks J-Nw+1 .. J-1 stay in the window; J-Nw leaves it and may go
     const float* se = a.se_blk + (size_t)unit * a.max_blocks;
     unsigned long long best = ~0ull;
     for (int s = lane; s < a.gpu_slots; s += kWave)

@@ -8,12 +8,16 @@
  - the fetch bound of Theorem 1 (n_load <= Kq after the first step, C = K) holds across block
    boundaries with the stated slot rule;
  - incremental facts: a new block gets a slot at its first token without a fetch, and is never
-   listed as a miss afterwards.
+   listed as a miss afterwards;
+ - the fetch bound over many budgets, the tight ones included (Kq = 0: nothing may ever be fetched
+   after the first step; Nw = 1: the block that leaves the window at a boundary must be allowed
+   to give up its slot; Ke = 0: it is the only block that can).
 """
 import numpy as np
+import pytest
 
 import oracle
-from helpers import oracle_params, to_np, widen
+from helpers import oracle_params, small_workload, to_np, widen
 from nosa_inputs import CONFIGS, QueryStream, append_token, make_layer
 
 
@@ -51,7 +55,7 @@ def test_append_places_tokens_and_keeps_attention_and_fetch_bound():
                         if len(empty):
                             assert s_new == empty[0]                             # lowest empty slot first
                         else:                                                    # else the least important candidate
-                            protect = max(w.window_blocks, 2)
+                            protect = w.window_blocks       # J-Nw+1 .. J-1 stay in the window
                             cand = [s for s in range(C) if w.sink_blocks <= bos_before[b, h, s] <= J - protect]
                             want = min(cand, key=lambda s: (prev_se[b, h, bos_before[b, h, s]], s))
                             assert s_new == want
@@ -81,3 +85,38 @@ def test_append_places_tokens_and_keeps_attention_and_fetch_bound():
                 pr = np.exp(z - z.max())
                 pr /= pr.sum()
                 np.testing.assert_allclose(out[b, hq], pr @ V64[b, h], rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("ns,nw,kq,ke", [(1, 1, 0, 1), (2, 1, 0, 0), (1, 1, 0, 2), (1, 2, 0, 1), (1, 3, 0, 2), (1, 1, 1, 1),
+                                         (2, 2, 1, 0), (1, 1, 2, 3), (1, 3, 2, 0)])
+def test_fetch_bound_holds_across_block_boundaries_for_tight_budgets(ns, nw, kq, ke):
+    K = ns + nw + kq + ke
+    for seed in (3, 17):
+        rng = np.random.default_rng(seed * 100 + K)
+        T = 64 * int(rng.integers(K, 2 * K + 3)) + int(rng.integers(0, 64))
+        steps = 150
+        w = small_workload(batch=1, n_q_heads=2, n_kv_heads=1, head_dim=64, context=T, k_blocks=K, kq_blocks=kq,
+                           sink_blocks=ns, window_blocks=nw, gpu_slots=K, dtype="fp32", generated=steps + 1,
+                           structure="key_offset" if seed == 3 else "drift")
+        p = oracle_params(w)
+        layer = make_layer(w, seed, 0)
+        hk, hv, hb = to_np(layer["host_k"]).copy(), to_np(layer["host_v"]).copy(), to_np(layer["host_bias"]).copy()
+        pk = np.zeros((1, 1, K, 64, 64), np.float32)
+        pv, pb = np.zeros_like(pk), np.zeros((1, 1, K, 64), np.float32)
+        sob, bos = np.full((1, 1, w.max_blocks), -1, np.int32), np.full((1, 1, K), -1, np.int32)
+        n_tok = np.full((1,), T, np.int32)
+        qs = QueryStream(w, seed, 0)
+        prev_se = np.full((1, 1, w.max_blocks), -np.inf)
+        for t in range(steps):
+            if t > 0:
+                tok = append_token(w, seed, 0, t)
+                oracle.append(p, to_np(tok["k_new"]), to_np(tok["v_new"]), to_np(tok["b_new"]), pk, pv, pb, hk, hv, hb,
+                              prev_se, n_tok, sob, bos)
+            kc, sec = oracle.pool(p, hk, hb, n_tok)
+            sq, se = oracle.block_score(p, to_np(qs.next(t)), kc, sec, n_tok)
+            prev_se = se
+            sel, n_sel = oracle.select(p, sq, se, n_tok)
+            ll, n_load = oracle.load(p, sel, n_sel, sob, bos)
+            oracle.fetch(p, hk, hv, hb, pk, pv, pb, ll, n_load)
+            if t > 0:
+                assert n_load.max() <= kq, f"seed {seed}, step {t}, T = {int(n_tok[0])}: {int(n_load.max())} blocks fetched, budget {kq}"

@@ -61,6 +61,8 @@ MUTANTS = [
      lambda: t_app.test_append_places_tokens_and_keeps_attention_and_fetch_bound()),
     ("new block evicts the most important resident block", "< se_blk[(int64_t)u * p->max_blocks + bos[best]]) best = s;", "> se_blk[(int64_t)u * p->max_blocks + bos[best]]) best = s;",
      lambda: t_app.test_append_places_tokens_and_keeps_attention_and_fetch_bound()),
+    ("the block that leaves the window may not give up its slot", "const int protect = p->window_blocks;", "const int protect = p->window_blocks > 2 ? p->window_blocks : 2;",
+     lambda: t_app.test_fetch_bound_holds_across_block_boundaries_for_tight_budgets(1, 1, 0, 1)),
     ("softplus without the linear part", "return (x > 0 ? x : 0) + log1p(exp(-fabs(x)));", "return log1p(exp(-fabs(x)));",
      lambda: t_ev.test_softplus_closed_forms_through_the_head()),
     ("eviction head reads the key instead of the value", "const int64_t vb = (int64_t)b * row + (int64_t)(Hq + Hkv + h) * d;", "const int64_t vb = (int64_t)b * row + (int64_t)(Hq + h) * d;",
