@@ -83,15 +83,16 @@ def draw_with_margin(w: Workload, qs: QueryStream, ol: OracleLayer, step: int, m
 
 
 def run_parity(w: Workload, seed: int, steps: int, device="cuda:0", overlap=True, check_attention=True,
-               residency=None, poison=True, margin=1e-3, layer_index=0):
+               residency=None, poison=True, margin=1e-3, layer_index=0, n_tokens=None):
     """Drives ``steps`` decode steps of one layer through both sides; asserts parity at each step.
 
+    ``n_tokens`` [B] gives every batch element its own token count (default: ``w.context`` for all).
     Returns per-step records (n_load, retries, max abs error)."""
     import paper_2510_13602_amd as nosa
     from paper_2510_13602_amd.runtime import LayerCache, pinned_like
 
     layer = make_layer(w, seed, layer_index)
-    n_tok = np.full((w.batch,), w.context, np.int32)
+    n_tok = np.full((w.batch,), w.context, np.int32) if n_tokens is None else np.asarray(n_tokens, np.int32)
     ol = OracleLayer(w, to_np(layer["host_k"]), to_np(layer["host_v"]), to_np(layer["host_bias"]), n_tok)
     ctx = nosa.Nosa(gpu_params(w), device=device)
     ctx.set_overlap(overlap)

@@ -57,6 +57,27 @@ def test_random_decode_steps(case):
 
 
 @pytest.mark.parametrize("case", range(8))
+def test_random_ragged_batches(case):
+    """Every batch element at its own token count, empty and one-token sequences included."""
+    rng = np.random.default_rng(1500 + case)
+    d, hkv, g = int(rng.choice([64, 128])), int(rng.choice([1, 2, 3])), int(rng.choice([1, 2, 4, 8]))
+    ns, nw, kq, ke = _budget(rng, False)
+    K = ns + nw + kq + ke
+    T = 64 * int(rng.integers(K, 4 * K + 8))
+    B = int(rng.integers(2, 6))
+    C = K + int(rng.integers(0, K + 1)) * int(rng.random() < 0.5)
+    pool = POOLS[int(rng.integers(0, len(POOLS)))]
+    w = small_workload(batch=B, n_q_heads=g * hkv, n_kv_heads=hkv, head_dim=d, context=T, k_blocks=K, kq_blocks=kq,
+                       sink_blocks=ns, window_blocks=nw, gpu_slots=C, dtype=str(rng.choice(["bf16", "fp32"])),
+                       structure=str(rng.choice(["planted", "key_offset", "ar1"])), pool_kernel=pool[0], pool_stride=pool[1],
+                       victim_policy=int(rng.random() < 0.4))
+    n_tok = rng.integers(0, T + 1, size=B).astype(np.int32)
+    n_tok[rng.integers(0, B)] = T
+    n_tok[rng.integers(0, B)] = int(rng.choice([0, 1, 63, 64, 65]))
+    _run(run_parity, w, int(rng.integers(0, 1 << 30)), steps=3, overlap=bool(rng.random() < 0.6), poison=False, n_tokens=n_tok)
+
+
+@pytest.mark.parametrize("case", range(8))
 def test_random_growing_context(case):
     rng = np.random.default_rng(2000 + case)
     d, hkv, g = int(rng.choice([64, 128])), int(rng.choice([1, 2])), int(rng.choice([1, 2, 4, 8]))
