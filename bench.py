@@ -270,8 +270,9 @@ def prefill_study(args):
     from nosa_inputs import CONFIGS, chunk_queries, make_layer
     dev = "cuda:0"
     B, lq = args.prefill_batch, args.prefill_chunk
-    w = CONFIGS["8b"].replace(batch=B)
+    w = CONFIGS[args.workload if args.workload in ("1b", "3b", "8b") else "8b"].replace(batch=B)
     w = w.replace(gpu_slots=w.max_blocks)
+    lq = min(lq, w.context)
     p0 = w.context - lq
     H, Hq, d, K = w.n_kv_heads, w.n_q_heads, w.head_dim, w.k_blocks
     stream = torch.cuda.Stream(device=dev)
@@ -335,7 +336,7 @@ def prefill_study(args):
         "metric": "sparse prefill tokens/sec (selection + attention of one layer)", "value": B * lq * args.steps / dt,
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": "8b-shaped sparse prefill, last chunk", "batch": B, "chunk": lq, "p0": p0, "n_q_heads": Hq,
+        "config": {"workload": f"{w.name}-shaped sparse prefill, last chunk", "batch": B, "chunk": lq, "p0": p0, "n_q_heads": Hq,
                    "n_kv_heads": H, "head_dim": d, "context": w.context, "k_blocks": K, "kq_blocks": w.kq_blocks,
                    "sink_blocks": w.sink_blocks, "window_blocks": w.window_blocks},
         "roofline": {"bound": "mfma", "achieved": flops / t_att / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
