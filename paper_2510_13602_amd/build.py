@@ -1,18 +1,24 @@
-"""Builds libnosa.so (hand-written HIP for gfx950 behind a C ABI) in-tree with hipcc."""
+"""Builds libnosa.so (hand-written HIP for gfx950 behind a C ABI) in-tree with hipcc.
+
+Every source is compiled to an object of its own (in parallel), then the objects are linked; with
+``force=False`` only the objects older than their source or than a header are compiled again.
+"""
 from __future__ import annotations
 
 import glob
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnosa.so")
 
 # packed fp32 instructions are switched off on purpose: the compiler otherwise forms them from
 # ordinary float code
-HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared", "-Wall",
+HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
@@ -20,20 +26,18 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+def _headers():
+    return glob.glob(os.path.join(CSRC, "*.h")) + [os.path.join(HERE, "..", "include", "nosa.h")]
+
+
 def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + [os.path.join(HERE, "..", "include", "nosa.h")]
-    return any(os.path.getmtime(f) > t for f in deps)
+    return any(os.path.getmtime(f) > t for f in sources() + _headers())
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile every HIP source into paper_2510_13602_amd/libnosa.so (cross-compiles without a GPU)."""
-    if not force and not is_stale():
-        return LIB
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + sources() + ["-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -41,11 +45,32 @@ def build(force: bool = True, verbose: bool = False) -> str:
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
         sys.stderr.write(res.stderr)
-        raise RuntimeError("hipcc failed")
+        raise RuntimeError("hipcc failed: " + " ".join(cmd))
     if verbose and err.strip():
         sys.stderr.write(err + "\n")
+
+
+def build(force: bool = True, verbose: bool = False, extra_flags=()) -> str:
+    """Compile every HIP source into paper_2510_13602_amd/libnosa.so (cross-compiles without a GPU)."""
+    if not force and not is_stale():
+        return LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ, exist_ok=True)
+    newest_header = max(os.path.getmtime(h) for h in _headers())
+    jobs, objs = [], []
+    for src in sources():
+        obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+        objs.append(obj)
+        fresh = os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header)
+        if force or extra_flags or not fresh:
+            jobs.append([hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-c", src, "-o", obj])
+    workers = max(1, min(len(jobs), os.cpu_count() or 1, 16))
+    if jobs:
+        with ThreadPoolExecutor(workers) as ex:
+            list(ex.map(lambda c: _run(c, verbose), jobs))
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build(force=True, verbose=True))
+    print(build(force="--incremental" not in sys.argv, verbose=True))
