@@ -210,8 +210,10 @@ int nosa_graph_destroy(nosa_graph* graph);
 /* Rebuilds k_pooled and se_pooled from a whole cache: K_c[j] = mean of the keys of sub-block j
  * (block compression f_c, Sec. 2.1), S_c^e[j] = mean of the importance score b over it (mean-pooling
  * Eq.).  keys [B,Hkv,max_blocks,n_b,d] and bias [B,Hkv,max_blocks,n_b] may be dev or pinned host
- * memory.  Accumulates in fp32, rounds K_c to dtype (nearest even).  Sub-blocks not complete at
- * n_tokens are written as zero.  Not part of the timed path.                                    */
+ * memory.  Sums in fp64 in token order and rounds once (K_c to dtype, nearest even; S_c^e to fp32), so
+ * the pooled arrays do not depend on any blocking of the sum and two implementations of this
+ * definition agree bit for bit.  Sub-blocks not complete at n_tokens are written as zero.  Not part
+ * of the timed path.                                                                            */
 int nosa_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const int32_t* n_tokens,
                      void* k_pooled, float* se_pooled);
 

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libnosa.so")
 
 NOSA_OK, NOSA_EINVAL, NOSA_ESHAPE, NOSA_EHIP = 0, -1, -2, -3
 DTYPE_F32, DTYPE_BF16 = 0, 1
-KERNEL_SCORE, KERNEL_SELECT, KERNEL_FETCH, KERNEL_DECODE, KERNEL_COMBINE, KERNEL_EVICT, KERNEL_APPEND = range(7)
+(KERNEL_SCORE, KERNEL_SELECT, KERNEL_FETCH, KERNEL_DECODE, KERNEL_COMBINE, KERNEL_EVICT, KERNEL_APPEND,
+ KERNEL_PREFILL) = range(8)
 KERNEL_NAMES = ["block_score", "select", "fetch", "sparse_decode", "combine", "split_qkv_evict", "append", "prefill_attend"]
 MAX_SPLITS = 16
 

@@ -244,6 +244,11 @@ static int prefill_check(nosa_ctx* ctx, const char* who, int p0, int lq) {
   NOSA_REQUIRE(ctx, (long long)p0 + lq <= (long long)p.max_blocks * p.block_size, NOSA_ESHAPE,
                "%s: p0 + lq = %lld exceeds the cache (%lld tokens)", who, (long long)p0 + lq,
                (long long)p.max_blocks * p.block_size);
+  // one pooled key per block: the selection reads se_pooled and the score scratch by block index
+  NOSA_REQUIRE(ctx, !(p.pool_kernel == p.block_size && p.pool_stride == p.block_size) ||
+                        (long long)p.n_sub_max * p.block_size >= (long long)p0 + lq,
+               NOSA_ESHAPE, "%s: n_sub_max (%d) pooled keys do not cover the %lld blocks of the prefix", who, p.n_sub_max,
+               ((long long)p0 + lq) / p.block_size);
   NOSA_REQUIRE(ctx, (long long)p.batch * lq * p.n_kv_heads <= (1 << 24), NOSA_ESHAPE,
                "%s: B * lq * Hkv = %lld exceeds %d positions x KV heads per call: split the chunk", who,
                (long long)p.batch * lq * p.n_kv_heads, 1 << 24);
@@ -294,9 +299,10 @@ int nosa_fetch(nosa_ctx* ctx, const void* host_k, const void* host_v, const floa
   NOSA_REQUIRE(ctx, (host_bias == nullptr) == (pool_bias == nullptr), NOSA_EINVAL,
                "nosa_fetch: host_bias and pool_bias must both be given or both be NULL");
   // The gather kernel dereferences the host pointers on the GPU: they must be page-locked and mapped.
+  // The query of the runtime is made once per pointer: a step that passes the same pools again pays nothing.
   const void* hp[3] = {host_k, host_v, host_bias};
   for (int i = 0; i < 3; ++i) {
-    if (!hp[i]) continue;
+    if (!hp[i] || hp[i] == ctx->host_ok[i]) continue;
     hipPointerAttribute_t at;
     hipError_t e = hipPointerGetAttributes(&at, hp[i]);
     if (e != hipSuccess) {
@@ -305,6 +311,7 @@ int nosa_fetch(nosa_ctx* ctx, const void* host_k, const void* host_v, const floa
     }
     NOSA_REQUIRE(ctx, at.type == hipMemoryTypeHost || at.type == hipMemoryTypeDevice || at.type == hipMemoryTypeManaged,
                  NOSA_EINVAL, "nosa_fetch: host pointer %d is pageable host memory", i);
+    ctx->host_ok[i] = hp[i];
   }
   hipStream_t s = ctx->main;
   if (ctx->overlap) {

@@ -46,6 +46,9 @@ struct nosa_ctx {
   void* ws = nullptr;
   size_t ws_bytes = 0;
   bool timing = false;
+  bool prefill_score_lds_set = false;    // dynamic-LDS limit of the prefill kernels raised (done once)
+  bool prefill_attend_lds_set = false;
+  const void* host_ok[3] = {nullptr, nullptr, nullptr};   // host pool pointers nosa_fetch has already vetted
   nosa::Timing timed[NOSA_KERNEL_COUNT];
   char err[512] = {0};
 };

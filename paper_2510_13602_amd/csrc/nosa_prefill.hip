@@ -3,15 +3,17 @@
 // causal prefix (selection Eq. of Sec. 3.1) and attends, with the eviction-head bias (Sec. 3.2),
 // to the tokens of its selected blocks that are not in its future.
 //
-// Unlike the decode step this is a dense contraction per selected block (32 positions x G heads
+// Unlike the decode step this is a dense contraction per selected block (64 positions x G heads
 // of queries against 64 keys), so it runs on the matrix cores: v_mfma_f32_32x32x16_bf16, fp32
 // accumulation, flash-style online softmax.
 //
-// One workgroup = 32 consecutive query positions of one (batch element, KV head), one wave = one
-// query head; two workgroups fit a CU (<= 256 registers per lane), so one's tile loads hide under
-// the other's arithmetic.  Positions that are neighbours select mostly the same blocks, so the
-// workgroup walks the UNION of their selections once; a 32-bit membership word per block says
-// which positions take part.  Per visited block:
+// One workgroup = 64 consecutive query positions of one (batch element, KV head) and up to four
+// query heads of its group; 8 waves, a wave = one query head x 32 positions (groups larger than
+// four take several workgroups).  256 registers per lane, so a SIMD holds two waves.  Positions
+// that are neighbours select mostly the same blocks, so the workgroup walks the UNION of their
+// selections once; a 64-bit membership word per block (built with LDS atomics from sel_idx, then
+// compacted into an ascending list by one wave) says which positions take part, the others get
+// p = 0.  Per visited block:
 //   S^T = K Q^T        A = K tile from LDS, B = Q^T held in registers for the whole kernel.
 //                      In the C layout a lane owns ONE query (column) and 16 keys per 32x32 tile,
 //                      so row max / row sum are in-lane plus one exchange with lane ^ 32.
@@ -22,10 +24,10 @@
 //                      swapped) and no cross-lane traffic is needed.
 // V arrives from HBM as [key][d]; it is transposed on its way into LDS (two keys packed per
 // 32-bit store).  Both LDS tiles are XOR-swizzled in 16-byte chunks so that the 16-byte operand
-// reads of eight neighbouring lanes fall into different banks.  The next block's rows are fetched
-// into registers while the current block is being multiplied.
+// reads of neighbouring lanes fall into different bank groups.  Two tile buffers: the next block's
+// rows are fetched into registers while the current block is being multiplied (one barrier per block).
 //
-// Workgroups are numbered so that the 64 that run together on one XCD (32 CUs x 2) are
+// Workgroups are numbered so that the ones that run together on one XCD (32 CUs) are
 // neighbouring query tiles of the same (batch element, KV head): they share most of their
 // blocks (the query-agnostic picks and overlapping windows), which then come from that XCD's L2.
 #include <cmath>
@@ -48,6 +50,7 @@ constexpr int kQ = 64;            // query positions per workgroup
 constexpr int kHeadsPerWg = 4;    // two waves each (32 positions per wave)
 constexpr int kXcds = 8;
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kMaxLds = 160 * 1024;   // LDS of one CU
 
 struct PrefillArgs {
   const void* q;             // [B, Lq, Hq, d]
@@ -453,13 +456,14 @@ int launch_prefill_score(nosa_ctx* ctx, const void* q_chunk, const void* k_poole
   const int n_hi = (p0 + lq) / kBlockTokens;
   const dim3 grid(lq / 32, ctx->units, (n_hi + 511) / 512);
   const size_t smem = (size_t)ctx->group * 32 * p.head_dim * 2;
-  NOSA_REQUIRE(ctx, smem <= 160 * 1024, NOSA_ESHAPE, "prefill: %d query heads per KV head need %zu bytes of LDS (limit 163840)",
+  NOSA_REQUIRE(ctx, smem <= (size_t)kMaxLds, NOSA_ESHAPE, "prefill: %d query heads per KV head need %zu bytes of LDS (limit 163840)",
                ctx->group, smem);
-  if (smem > 64 * 1024) {
+  if (smem > 64 * 1024 && !ctx->prefill_score_lds_set) {   // once per context: raise the kernel's LDS limit to the CU's
     if (p.head_dim == 128)
-      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_score_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_score_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds));
     else
-      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_score_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_score_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds));
+    ctx->prefill_score_lds_set = true;
   }
   NOSA_REQUIRE(ctx, ctx->units <= 65535 && grid.z <= 65535, NOSA_ESHAPE, "prefill: B * Hkv = %d exceeds 65535", ctx->units);
   TimedLaunch tl(ctx, NOSA_KERNEL_SCORE, ctx->main);
@@ -479,13 +483,14 @@ int launch_prefill_attend(nosa_ctx* ctx, const void* q_chunk, const void* cache_
                 p.n_q_heads, p.max_blocks, p.k_blocks, p0, lq, ctx->units, n_qt, n_hz, list_cap, ctx->scale};
   const size_t tile = (size_t)kBlockTokens * p.head_dim * 2 + (size_t)p.head_dim * 128 + 64 * sizeof(float);
   const size_t smem = 2 * tile + 16 + (size_t)list_cap * 20;
-  NOSA_REQUIRE(ctx, smem <= 160 * 1024, NOSA_ESHAPE, "prefill: %d blocks of context need %zu bytes of LDS (limit 163840)",
+  NOSA_REQUIRE(ctx, smem <= (size_t)kMaxLds, NOSA_ESHAPE, "prefill: %d blocks of context need %zu bytes of LDS (limit 163840)",
                list_cap, smem);
-  if (smem > 64 * 1024) {
+  if (smem > 64 * 1024 && !ctx->prefill_attend_lds_set) {
     if (p.head_dim == 128)
-      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_attend_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_attend_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds));
     else
-      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_attend_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      NOSA_HIP(ctx, hipFuncSetAttribute((const void*)prefill_attend_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds));
+    ctx->prefill_attend_lds_set = true;
   }
   const long long wgs = (long long)kXcds * ((ctx->units + kXcds - 1) / kXcds) * n_qt * n_hz;
   NOSA_REQUIRE(ctx, wgs <= 0x7fffffffLL, NOSA_ESHAPE, "prefill: too many workgroups (%lld)", wgs);

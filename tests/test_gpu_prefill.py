@@ -64,6 +64,11 @@ def test_prefill_rejects_what_it_does_not_support():
     with pytest.raises(nosa.NosaError, match="gpu_slots"):
         ctx.nosa_prefill_attend(q, kv2, kv2, bias2, sel, n_sel, 0, lq, out, lse)
     ctx.close()
+    # fewer pooled keys than blocks in the prefix: the selection would read past the pooled arrays
+    ctx = nosa.Nosa(gpu_params(w, n_sub_max=4))
+    with pytest.raises(nosa.NosaError, match="pooled keys do not cover"):
+        ctx.nosa_prefill_attend(q, kv, kv, bias, sel, n_sel, 64 * 5, lq, out, lse)
+    ctx.close()
     w3 = small_workload(batch=1, context=64 * 8, gpu_slots=8, dtype="fp32", k_blocks=6)
     ctx = nosa.Nosa(gpu_params(w3))
     with pytest.raises(nosa.NosaError, match="bf16 only"):
