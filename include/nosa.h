@@ -166,6 +166,22 @@ int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const v
                        const float* pool_bias, const int32_t* sel_idx, const int32_t* n_sel,
                        const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse);
 
+/* nosa_sparse_decode for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same
+ * kernels and same result, but the split partial results live in a scratch array of
+ * NOSA_STATIC_SCRATCH_BYTES that is part of the library's device code (one copy per GPU, held until the
+ * process ends) instead of in the workspace of nosa_set_workspace, which need not be set.  The call
+ * allocates nothing.  It needs units x splits x G x (d + 2) x 4 bytes and returns NOSA_ESHAPE when
+ * that exceeds the array (lower nosa_set_splits, or use nosa_sparse_decode).  Nothing in the array
+ * has to start at zero: every partial result is written before it is read.  All contexts of a process
+ * share a GPU's array and it keeps the last call's contents, so two such calls that overlap in time
+ * on one GPU (different streams, or a graph replay beside an eager call) race; calls on one stream
+ * are ordered.                                                                                     */
+#define NOSA_STATIC_SCRATCH_BYTES (8u << 20)
+int nosa_sparse_decode_static(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v,
+                              const float* pool_bias, const int32_t* sel_idx, const int32_t* n_sel,
+                              const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse);
+
 /* One whole decode step of one layer = the four calls above, in the order of Alg. 1, behind one
  * entry point (one boundary crossing per step instead of four).  Every field has the meaning and
  * memory kind of the like-named argument above; host_bias / pool_bias may both be NULL, lse may be

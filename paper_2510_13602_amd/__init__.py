@@ -4,5 +4,5 @@
 """
 from .binding import (DTYPE_BF16, DTYPE_F32, EXPORTS, KERNEL_APPEND, KERNEL_COMBINE, KERNEL_DECODE,  # noqa: F401
                       KERNEL_EVICT, KERNEL_FETCH, KERNEL_NAMES, KERNEL_PREFILL,
-                      KERNEL_SCORE, KERNEL_SELECT, LIB_PATH, MAX_SPLITS, Nosa, NosaError, Params, StepArgs,
+                      KERNEL_SCORE, KERNEL_SELECT, LIB_PATH, MAX_SPLITS, Nosa, NosaError, Params, STATIC_SCRATCH_BYTES, StepArgs,
                       load_library, make_params, validate_params)

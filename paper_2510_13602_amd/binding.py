@@ -21,11 +21,12 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
  KERNEL_PREFILL) = range(8)
 KERNEL_NAMES = ["block_score", "select", "fetch", "sparse_decode", "combine", "split_qkv_evict", "append", "prefill_attend"]
 MAX_SPLITS = 16
+STATIC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = [
     "nosa_validate_params", "nosa_create", "nosa_destroy", "nosa_workspace_bytes", "nosa_set_workspace",
     "nosa_set_splits", "nosa_get_splits", "nosa_set_overlap", "nosa_set_fetch_workgroups", "nosa_last_error", "nosa_block_score",
-    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_fetch_tokens", "nosa_decode_step", "nosa_graph_create", "nosa_graph_launch",
+    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_sparse_decode_static", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_fetch_tokens", "nosa_decode_step", "nosa_graph_create", "nosa_graph_launch",
     "nosa_graph_destroy", "nosa_prefill_select", "nosa_prefill_attend", "nosa_timing_enable",
     "nosa_timing_read",
 ]
@@ -82,6 +83,7 @@ def load_library() -> ctypes.CDLL:
     lib.nosa_select.argtypes = [vp, fp, fp, i32p, i32p, i32p, i32p, i32p, i32p, i32p]
     lib.nosa_fetch.argtypes = [vp, vp, vp, fp, vp, vp, fp, i32p, i32p]
     lib.nosa_sparse_decode.argtypes = [vp, vp, vp, vp, fp, i32p, i32p, i32p, i32p, vp, fp]
+    lib.nosa_sparse_decode_static.argtypes = lib.nosa_sparse_decode.argtypes
     lib.nosa_pool_blocks.argtypes = [vp, vp, fp, i32p, vp, fp]
     lib.nosa_append.argtypes = [vp] + [vp] * 15
     lib.nosa_split_qkv_evict.argtypes = [vp, vp, fp, fp, ctypes.c_int, vp, vp, vp, fp]
@@ -140,7 +142,7 @@ def _raw(t: torch.Tensor, dtype, shape, name: str):
 class Nosa:
     """One context = one layer shape (see ``nosa_create``).  Methods mirror the C entry points."""
 
-    def __init__(self, params: Params, stream: Optional[torch.cuda.Stream] = None, device="cuda:0"):
+    def __init__(self, params: Params, stream: Optional[torch.cuda.Stream] = None, device="cuda:0", workspace: bool = True):
         self.lib = load_library()
         if not torch.cuda.is_available():
             raise NosaError(NOSA_EHIP, "no GPU: the NOSA hot path has no CPU fallback")
@@ -152,9 +154,11 @@ class Nosa:
             rc = self.lib.nosa_create(ctypes.byref(self._ctx), ctypes.byref(params), ctypes.c_void_p(self.stream.cuda_stream))
         if rc != NOSA_OK:
             raise NosaError(rc, self.lib.nosa_last_error(None).decode())
-        nbytes = self.lib.nosa_workspace_bytes(ctypes.byref(params))
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-        self._check(self.lib.nosa_set_workspace(self._ctx, ctypes.c_void_p(self.workspace.data_ptr()), nbytes))
+        self.workspace = None
+        if workspace:
+            nbytes = self.lib.nosa_workspace_bytes(ctypes.byref(params))
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self._check(self.lib.nosa_set_workspace(self._ctx, ctypes.c_void_p(self.workspace.data_ptr()), nbytes))
         self.tdtype = torch.float32 if params.dtype == DTYPE_F32 else torch.bfloat16
 
     # -- plumbing ------------------------------------------------------------------------------
@@ -239,10 +243,13 @@ class Nosa:
             _dev(load_list, torch.int32, (B, H, p.k_blocks, 2), "load_list"),
             _dev(n_load, torch.int32, (B, H), "n_load")))
 
-    def nosa_sparse_decode(self, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse=None) -> None:
+    def nosa_sparse_decode(self, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse=None,
+                           static_scratch: bool = False) -> None:
+        """``static_scratch=True`` calls nosa_sparse_decode_static (split results in the library's own array)."""
         p, B, H = self.p, self._B, self._H
         kv_pool = (B, H, p.gpu_slots, p.block_size, p.head_dim)
-        self._check(self.lib.nosa_sparse_decode(
+        fn = self.lib.nosa_sparse_decode_static if static_scratch else self.lib.nosa_sparse_decode
+        self._check(fn(
             self._ctx, _dev(q, self.tdtype, (B, p.n_q_heads, p.head_dim), "q"),
             _dev(pool_k, self.tdtype, kv_pool, "pool_k"), _dev(pool_v, self.tdtype, kv_pool, "pool_v"),
             _dev(pool_bias, torch.float32, kv_pool[:4], "pool_bias"),

@@ -19,6 +19,7 @@
 //
 // Logits are kept in the log2 domain: z' = (scale*log2 e) q.k + b*log2 e, p = 2^(z' - m').
 #include <cmath>
+#include <mutex>
 
 #include "nosa_device.h"
 #include "nosa_internal.h"
@@ -448,6 +449,39 @@ bool dispatch_group(int g, const DecodeArgs& a, dim3 grid, hipStream_t s) {
 
 }  // namespace
 
+// Scratch of the allocation-free entry point (nosa_sparse_decode_static): one array per GPU, part of the
+// loaded code object, alive until the process ends.  In host code the array's name is only a handle of
+// the symbol, not a device address: the address on a given GPU comes from hipGetSymbolAddress with that
+// GPU current, and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[NOSA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};   // address of `scratch` on each device, looked up once
+}  // namespace
+
+// Address of the static scratch on `device`, which must be the current device.
+int decode_static_scratch(nosa_ctx* ctx, int device, void** out) {
+  NOSA_REQUIRE(ctx, device >= 0 && device < kMaxDevices, NOSA_ESHAPE, "device %d: the static scratch is kept for devices 0..%d",
+               device, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    NOSA_HIP(ctx, hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+    NOSA_REQUIRE(ctx, ptr != nullptr && ((uintptr_t)ptr & 255) == 0, NOSA_EHIP,
+                 "hipGetSymbolAddress returned %p for the static scratch", ptr);
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return NOSA_OK;
+}
+
+// Bytes of split partial results one decode call keeps in its scratch: O[G][D] and (m, l)[G] per (unit, split).
+size_t decode_partial_bytes(const nosa_ctx* ctx) {
+  return (size_t)ctx->units * ctx->splits * ctx->group * (size_t)(ctx->p.head_dim + 2) * sizeof(float);
+}
+
 bool decode_supports_group(int g) {
   return g == 1 || g == 2 || g == 3 || g == 4 || g == 6 || g == 8 || g == 12 || g == 16;
 }
@@ -486,13 +520,13 @@ bool dispatch(const nosa_params& p, int G, const DecodeArgs& a, dim3 grid, hipSt
 int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v, const float* pool_bias,
                   const int32_t* sel_idx, const int32_t* n_sel, const int32_t* slot_of_block,
                   const int32_t* n_tokens, void* out, float* lse, hipEvent_t wait_fetch,
-                  const int32_t* load_list, const int32_t* n_load) {
+                  const int32_t* load_list, const int32_t* n_load, void* ws) {
   const nosa_params& p = ctx->p;
   const int G = ctx->group, D = p.head_dim, S = ctx->splits;
   DecodeArgs a;
   a.q = q; a.pool_k = pool_k; a.pool_v = pool_v; a.pool_bias = pool_bias;
   a.sel_idx = sel_idx; a.n_sel = n_sel; a.slot_of_block = slot_of_block; a.n_tokens = n_tokens;
-  a.part_o = (float*)ctx->ws;
+  a.part_o = (float*)ws;   // scratch of the split partial results: the caller's workspace or the static array
   a.part_ml = a.part_o ? a.part_o + (size_t)ctx->units * S * G * D : nullptr;
   a.out = out; a.lse = lse;
   a.load_list = load_list; a.n_load = n_load;

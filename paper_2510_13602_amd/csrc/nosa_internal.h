@@ -45,6 +45,7 @@ struct nosa_ctx {
   int fetch_wgs = 512;      // workgroups of the gather kernel (capped by the number of units)
   void* ws = nullptr;
   size_t ws_bytes = 0;
+  void* static_scratch = nullptr;   // this device's copy of the library's static scratch array
   bool timing = false;
   bool prefill_score_lds_set = false;    // dynamic-LDS limit of the prefill kernels raised (done once)
   bool prefill_attend_lds_set = false;
@@ -98,7 +99,9 @@ int launch_fetch(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const vo
 int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v,
                   const float* pool_bias, const int32_t* sel_idx, const int32_t* n_sel,
                   const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse,
-                  hipEvent_t wait_fetch, const int32_t* load_list, const int32_t* n_load);
+                  hipEvent_t wait_fetch, const int32_t* load_list, const int32_t* n_load, void* ws);
+int decode_static_scratch(nosa_ctx* ctx, int device, void** out);
+size_t decode_partial_bytes(const nosa_ctx* ctx);
 int launch_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const int32_t* n_tokens,
                        void* k_pooled, float* se_pooled);
 int launch_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float* b_new, void* pool_k, void* pool_v,
