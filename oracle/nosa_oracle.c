@@ -39,7 +39,8 @@
  * Parity pins (tests/test_oracle_*.py): brute-force dense attention restricted to Gamma,
  * textbook softmax attention when everything is selected and b = 0, exhaustive subset
  * search for the selection on tiny inputs, the single-pass +inf formulation of
- * Eq. (selection), linearity of pooled-key scoring, the locality bound of Theorem 1.
+ * Eq. (selection), linearity of pooled-key scoring, the locality bound of Theorem 1;
+ * oracle_fetch_tokens against a fancy-index row gather and against oracle_fetch on whole blocks.
  * Unpinned (readings, no printed values exist in the paper): the choices listed above.
  */
 #include <math.h>

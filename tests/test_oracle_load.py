@@ -173,3 +173,82 @@ def test_importance_ranked_victims_against_brute_force():
                               else (1, se[b, h, before_bos[b, h, s]], s))
                 want = sorted(rank[:len(miss)])
                 assert ll[b, h, :n_load[b, h], 1].tolist() == want
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_token_fetch_is_a_row_gather(dtype):
+    """Element-wise transfer (Sec. 3.2 "Comparison with DMA"): copying listed token rows is, by definition, a
+    gather/scatter of rows, which numpy's fancy indexing states in one line per tensor.  Lists of every length
+    from empty to the whole pool, distinct destinations; rows not listed must keep their old bytes; entries
+    beyond n_list must be ignored."""
+    rng = np.random.default_rng(5 if dtype == "bf16" else 6)
+    w = small_workload(batch=2, n_q_heads=4, n_kv_heads=2, head_dim=64, context=64 * 9, k_blocks=4, kq_blocks=1,
+                       gpu_slots=5, dtype=dtype)
+    p = oracle_params(w)
+    layer = make_layer(w, 31, 0)
+    hk, hv, hb = to_np(layer["host_k"]), to_np(layer["host_v"]), to_np(layer["host_bias"])
+    B, H, C, nb, d, N = w.batch, w.n_kv_heads, w.gpu_slots, w.block_size, w.head_dim, w.max_blocks
+    M = C * nb
+    lengths = np.array([[0, M], [1, 77]], np.int32)                 # empty, full, one row, ragged
+    tl = np.full((B, H, M, 2), -1, np.int32)
+    for b in range(B):
+        for h in range(H):
+            n = lengths[b, h]
+            tl[b, h, :n, 0] = rng.choice(N * nb, n, replace=False)
+            tl[b, h, :n, 1] = rng.choice(C * nb, n, replace=False)
+            tl[b, h, n:, 0] = rng.integers(0, N * nb, M - n)         # junk beyond the list length
+            tl[b, h, n:, 1] = rng.integers(0, C * nb, M - n)
+    old_k = rng.integers(0, 2 ** 16, (B, H, C, nb, d)).astype(hk.dtype) if hk.dtype == np.uint16 \
+        else rng.standard_normal((B, H, C, nb, d)).astype(np.float32)
+    old_v = old_k[..., ::-1].copy()
+    old_b = rng.standard_normal((B, H, C, nb)).astype(np.float32)
+    pk, pv, pb = old_k.copy(), old_v.copy(), old_b.copy()
+    oracle.fetch_tokens(p, hk, hv, hb, pk, pv, pb, tl, lengths)
+    for b in range(B):
+        for h in range(H):
+            n = lengths[b, h]
+            src, dst = tl[b, h, :n, 0], tl[b, h, :n, 1]
+            want_k, want_v, want_b = old_k[b, h].reshape(M, d).copy(), old_v[b, h].reshape(M, d).copy(), old_b[b, h].reshape(M).copy()
+            want_k[dst] = hk[b, h].reshape(N * nb, d)[src]
+            want_v[dst] = hv[b, h].reshape(N * nb, d)[src]
+            want_b[dst] = hb[b, h].reshape(N * nb)[src]
+            assert pk[b, h].reshape(M, d).tobytes() == want_k.tobytes()
+            assert pv[b, h].reshape(M, d).tobytes() == want_v.tobytes()
+            assert pb[b, h].reshape(M).tobytes() == want_b.tobytes()
+    # bias pointers may be absent: keys and values still move, the bias pool is left alone
+    pk2, pv2 = old_k.copy(), old_v.copy()
+    oracle.fetch_tokens(p, hk, hv, None, pk2, pv2, None, tl, lengths)
+    assert pk2.tobytes() == pk.tobytes() and pv2.tobytes() == pv.tobytes()
+
+
+def test_token_fetch_of_whole_blocks_equals_block_fetch():
+    """A block-wise load list expanded into its 64 token rows must give the same pool as the block-wise fetch."""
+    rng = np.random.default_rng(9)
+    w = small_workload(batch=2, n_q_heads=4, n_kv_heads=2, head_dim=64, context=64 * 12, k_blocks=6, kq_blocks=2,
+                       gpu_slots=6, dtype="bf16")
+    p = oracle_params(w)
+    layer = make_layer(w, 32, 0)
+    hk, hv, hb = to_np(layer["host_k"]), to_np(layer["host_v"]), to_np(layer["host_bias"])
+    B, H, C, nb, d, K = w.batch, w.n_kv_heads, w.gpu_slots, w.block_size, w.head_dim, w.k_blocks
+    ll = np.full((B, H, K, 2), -1, np.int32)
+    n_load = rng.integers(0, K + 1, (B, H)).astype(np.int32)
+    tl = np.full((B, H, K * nb, 2), -1, np.int32)
+    for b in range(B):
+        for h in range(H):
+            n = n_load[b, h]
+            ll[b, h, :n, 0] = np.sort(rng.choice(w.max_blocks, n, replace=False))
+            ll[b, h, :n, 1] = rng.choice(C, n, replace=False)
+            for i in range(n):
+                tl[b, h, i * nb:(i + 1) * nb, 0] = ll[b, h, i, 0] * nb + np.arange(nb)
+                tl[b, h, i * nb:(i + 1) * nb, 1] = ll[b, h, i, 1] * nb + np.arange(nb)
+    pools = []
+    for mode in ("block", "token"):
+        pk, pv = np.zeros((B, H, C, nb, d), hk.dtype), np.zeros((B, H, C, nb, d), hv.dtype)
+        pb = np.zeros((B, H, C, nb), np.float32)
+        if mode == "block":
+            oracle.fetch(p, hk, hv, hb, pk, pv, pb, ll, n_load)
+        else:
+            oracle.fetch_tokens(p, hk, hv, hb, pk, pv, pb, tl, (n_load * nb).astype(np.int32))
+        pools.append((pk, pv, pb))
+    for x, y in zip(*pools):
+        assert x.tobytes() == y.tobytes()

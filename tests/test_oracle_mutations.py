@@ -63,6 +63,12 @@ MUTANTS = [
      lambda: t_app.test_append_places_tokens_and_keeps_attention_and_fetch_bound()),
     ("the block that leaves the window may not give up its slot", "const int protect = p->window_blocks;", "const int protect = p->window_blocks > 2 ? p->window_blocks : 2;",
      lambda: t_app.test_fetch_bound_holds_across_block_boundaries_for_tight_budgets(1, 1, 0, 1)),
+    ("token fetch reads the host row at the pool's row index", "const size_t src = (size_t)u * p->max_blocks * nb + t, dst = (size_t)u * C * nb + r;",
+     "const size_t src = (size_t)u * p->max_blocks * nb + r, dst = (size_t)u * C * nb + r;",
+     lambda: t_load.test_token_fetch_is_a_row_gather("bf16")),
+    ("token fetch copies the key row into the value pool", "memcpy((char *)pool_v + dst * rowb, (const char *)host_v + src * rowb, rowb);",
+     "memcpy((char *)pool_v + dst * rowb, (const char *)host_k + src * rowb, rowb);",
+     lambda: t_load.test_token_fetch_of_whole_blocks_equals_block_fetch()),
     ("softplus without the linear part", "return (x > 0 ? x : 0) + log1p(exp(-fabs(x)));", "return log1p(exp(-fabs(x)));",
      lambda: t_ev.test_softplus_closed_forms_through_the_head()),
     ("eviction head reads the key instead of the value", "const int64_t vb = (int64_t)b * row + (int64_t)(Hq + Hkv + h) * d;", "const int64_t vb = (int64_t)b * row + (int64_t)(Hq + h) * d;",
