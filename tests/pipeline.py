@@ -157,8 +157,9 @@ def run_parity(w: Workload, seed: int, steps: int, device="cuda:0", overlap=True
 
 
 def run_fullsize_sampled(w: Workload, seed: int, steps: int, n_samples: int, device="cuda:0", margin=1e-3):
-    """A workload at its full size, in the launch configuration ``bench.py`` times (default splits,
-    fetch on the side stream, cold start through the real path), checked two ways:
+    """A workload at its full size with the library's default stream order (default splits, fetch on the
+    side stream, attention in two launches around it, cold start through the real path), checked two ways
+    (``run_fullsize_all_units`` covers the one-stream order that ``bench.py`` times):
 
     * sampled units: each is re-run by the oracle as a one-unit problem on the same bytes, with its
       residency state carried along; Gamma, miss count and the attention rows must match;
@@ -248,16 +249,91 @@ def run_fullsize_sampled(w: Workload, seed: int, steps: int, n_samples: int, dev
     return worst
 
 
-def run_growing(w: Workload, seed: int, steps: int, device="cuda:0", margin=1e-3, check_every=1):
+def run_fullsize_all_units(w: Workload, seed: int, layer_index: int, steps: int, attention_steps, mode: str,
+                           device="cuda:0", margin=1e-3):
+    """A workload at its full size, EVERY unit against the oracle at EVERY step: Gamma, its length, the miss
+    count, the load list and both residency maps bit for bit; the attention output of every unit on the steps
+    in ``attention_steps``; at the end the whole GPU pool byte for byte against the oracle's.
+
+    ``mode`` picks the launch configuration: "fused" is what ``bench.py`` times (everything on one stream
+    through the single ``nosa_decode_step`` entry: the plain attention kernel, default splits); "overlap" is
+    the library's default order (gather on the side stream, attention in two launches around it).
+    The layer (index ``layer_index`` of the workload's stack) is drawn on the GPU and copied to pinned host
+    memory once; the oracle reads those very bytes.
+    """
+    import paper_2510_13602_amd as nosa
+    from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+
+    assert mode in ("fused", "overlap")
+    attention_steps = set(attention_steps)
+    print(f"all units {w.name} layer {layer_index} ({mode}): drawing the layer on the GPU", flush=True)
+    layer = make_layer(w, seed, layer_index, device=device)
+    hk, hv, hb = pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"])
+    del layer
+    torch.cuda.empty_cache()
+    n_tok = np.full((w.batch,), w.context, np.int32)
+    ol = OracleLayer(w, to_np(hk), to_np(hv), to_np(hb), n_tok)
+    ctx = nosa.Nosa(gpu_params(w), device=device)
+    ctx.set_overlap(mode == "overlap")
+    gl = LayerCache(ctx, hk, hv, hb, torch.from_numpy(n_tok))
+    gl.rebuild_pooled()
+    torch.cuda.synchronize()
+    assert to_np(gl.k_pooled).tobytes() == ol.kc.tobytes()
+    assert to_np(gl.se_pooled).tobytes() == ol.sec.tobytes()
+    gl.pool_k.fill_(float("nan")); gl.pool_v.fill_(float("nan")); gl.pool_bias.fill_(float("nan"))
+    ol.pk[...] = 0x7fc0 if ol.pk.dtype == np.uint16 else np.nan
+    ol.pv[...] = 0x7fc0 if ol.pv.dtype == np.uint16 else np.nan
+    ol.pb[...] = np.nan
+    qs = QueryStream(w, seed, layer_index, device=device)
+    worst, retries_total, loads = 0.0, 0, []
+    for t in range(steps):
+        q, retries = draw_with_margin(w, qs, ol, t, margin)
+        retries_total += retries
+        att = t in attention_steps
+        ref = ol.step(to_np(q), attention=att)
+        out = gl.step_fused(q) if mode == "fused" else gl.step(q)
+        torch.cuda.synchronize()
+        assert (gl.sel_idx.cpu().numpy() == ref["sel"]).all(), f"step {t}: selected blocks differ"
+        assert (gl.n_sel.cpu().numpy() == ref["n_sel"]).all()
+        assert (gl.n_load.cpu().numpy() == ref["n_load"]).all(), f"step {t}: miss counts differ"
+        assert (gl.load_list.cpu().numpy() == ref["load_list"]).all(), f"step {t}: load lists differ"
+        assert (gl.slot_of_block.cpu().numpy() == ol.sob).all() and (gl.block_of_slot.cpu().numpy() == ol.bos).all()
+        if t == 0:
+            assert (ref["n_load"] == min(w.k_blocks, w.max_blocks)).all()
+        elif w.gpu_slots == w.k_blocks:
+            assert ref["n_load"].max() <= w.kq_blocks, f"step {t}: fetch bound broken"          # Theorem 1
+        if t > 0:
+            loads.append(float(ref["n_load"].mean()))
+        if att:
+            got = out.double().cpu().numpy()
+            assert np.isfinite(got).all(), f"step {t}: non-finite output"
+            err = float(np.abs(got - ref["out"]).max())
+            worst = max(worst, err)
+            assert err <= out_tol(w.dtype), f"step {t}: max abs err {err}"
+            lerr = float(np.abs(gl.lse.double().cpu().numpy() - ref["lse"]).max())
+            assert lerr <= 1e-3, f"step {t}: lse err {lerr}"
+        if t % 16 == 0 or t == steps - 1:
+            print(f"all units {w.name} layer {layer_index} ({mode}) step {t}: n_load mean {ref['n_load'].mean():.2f} "
+                  f"max {ref['n_load'].max()}, worst attention err so far {worst:.2e}", flush=True)
+    assert to_np(gl.pool_k).tobytes() == ol.pk.tobytes() and to_np(gl.pool_v).tobytes() == ol.pv.tobytes()
+    assert to_np(gl.pool_bias).tobytes() == ol.pb.tobytes()
+    ctx.close()
+    return dict(worst=worst, retries=retries_total, mean_load=float(np.mean(loads)) if loads else 0.0)
+
+
+def run_growing(w: Workload, seed: int, steps: int, device="cuda:0", margin=1e-3, check_every=1, attention_steps=None,
+                progress=0):
     """Growing context: every step after the first appends one token per unit (key, value, bias)
-    before scoring, on both sides; all state (pool, maps, pooled arrays, token counts) is compared.
+    before scoring, on both sides; the integer state (token counts, Gamma, miss counts, load lists, both
+    maps) is compared at EVERY step.  Pooled arrays and the attention output are compared on the steps
+    of ``attention_steps`` (default: every ``check_every``-th step and the steps around block boundaries).
     Also asserts the fetch bound n_load <= Kq at every step after the first, block boundaries included.
     """
     import paper_2510_13602_amd as nosa
     from nosa_inputs import append_token
     from paper_2510_13602_amd.runtime import LayerCache, pinned_like
 
-    assert w.generated >= steps
+    assert w.generated >= steps - 1          # step 0 appends nothing
     layer = make_layer(w, seed, 0)
     n_tok = np.full((w.batch,), w.context, np.int32)
     ol = OracleLayer(w, to_np(layer["host_k"]).copy(), to_np(layer["host_v"]).copy(), to_np(layer["host_bias"]).copy(), n_tok)
@@ -267,16 +343,26 @@ def run_growing(w: Workload, seed: int, steps: int, device="cuda:0", margin=1e-3
     gl.rebuild_pooled()
     qs = QueryStream(w, seed, 0)
     prev_se = np.full((w.batch, w.n_kv_heads, w.max_blocks), -np.inf)
-    boundary_loads, worst = [], 0.0
+    boundary_loads, worst, checked = [], 0.0, 0
+
+    def n_sub(T):                     # complete sub-blocks of a cache of T tokens
+        return 0 if T < w.pool_kernel else (T - w.pool_kernel) // w.pool_stride + 1
+
     for t in range(steps):
         if t > 0:
             tok = append_token(w, seed, 0, t)
+            before = n_sub(int(ol.n_tok[0]))
             oracle.append(ol.p, to_np(tok["k_new"]), to_np(tok["v_new"]), to_np(tok["b_new"]), ol.pk, ol.pv, ol.pb,
                           ol.hk, ol.hv, ol.hb, prev_se, ol.n_tok, ol.sob, ol.bos)
-            ol.kc, ol.sec = oracle.pool(ol.p, ol.hk, ol.hb, ol.n_tok)
+            if n_sub(int(ol.n_tok[0])) != before:       # the pooled arrays only change when a sub-block completes
+                ol.kc, ol.sec = oracle.pool(ol.p, ol.hk, ol.hb, ol.n_tok)
             gl.append(tok["k_new"].to(device), tok["v_new"].to(device), tok["b_new"].to(device))
         q, _ = draw_with_margin(w, qs, ol, t, margin)
-        ref = ol.step(to_np(q))
+        if attention_steps is None:
+            check = t % check_every == 0 or (w.context + t) % w.block_size in (0, 1, w.block_size - 1)
+        else:
+            check = t in attention_steps
+        ref = ol.step(to_np(q), attention=check)
         prev_se = ref["se"]
         out = gl.step(q.to(device))
         torch.cuda.synchronize()
@@ -289,7 +375,11 @@ def run_growing(w: Workload, seed: int, steps: int, device="cuda:0", margin=1e-3
             assert ref["n_load"].max() <= w.kq_blocks, f"step {t}: fetch bound broken ({ref['n_load'].max()})"
         if (w.context + t) % w.block_size == 0:
             boundary_loads.append(int(ref["n_load"].max()))
-        if t % check_every == 0 or (w.context + t) % w.block_size in (0, 1, w.block_size - 1):
+        if progress and t % progress == 0:
+            print(f"growing {w.name}: step {t} of {steps}, {int(ol.n_tok[0])} tokens, n_load max {int(ref['n_load'].max())}, "
+                  f"{checked} attention checks, worst err {worst:.2e}", flush=True)
+        if check:
+            checked += 1
             assert to_np(gl.k_pooled).tobytes() == ol.kc.tobytes(), f"step {t}: pooled keys differ"
             assert to_np(gl.se_pooled).tobytes() == ol.sec.tobytes(), f"step {t}: pooled importance differs"
             got = out.double().cpu().numpy()
@@ -301,8 +391,12 @@ def run_growing(w: Workload, seed: int, steps: int, device="cuda:0", margin=1e-3
     torch.cuda.synchronize()
     assert to_np(gl.host_k).tobytes() == ol.hk.tobytes() and to_np(gl.host_v).tobytes() == ol.hv.tobytes()
     assert to_np(gl.host_bias).tobytes() == ol.hb.tobytes()
+    # ... and the pooled arrays and the GPU pool ended up identical to the oracle's
+    assert to_np(gl.k_pooled).tobytes() == ol.kc.tobytes() and to_np(gl.se_pooled).tobytes() == ol.sec.tobytes()
+    assert to_np(gl.pool_k).tobytes() == ol.pk.tobytes() and to_np(gl.pool_v).tobytes() == ol.pv.tobytes()
+    assert to_np(gl.pool_bias).tobytes() == ol.pb.tobytes()
     ctx.close()
-    return dict(worst=worst, boundary_loads=boundary_loads)
+    return dict(worst=worst, boundary_loads=boundary_loads, checked=checked)
 
 
 # ---- sparse prefill --------------------------------------------------------------------------------

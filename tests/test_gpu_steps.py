@@ -31,8 +31,16 @@ def test_1b_shaped_half_resident():
     """batch 16, 16 q heads / 2 KV heads, d64, 8192 tokens, C = 64 of 128 blocks resident at start."""
     w = CONFIGS["1b"]
     res = random_residency(w, seed=0, layer=0, n_blocks=w.context // w.block_size)
-    rec = run_parity(w, seed=0, steps=12, residency=res)
+    rec = run_parity(w, seed=0, steps=w.steps, residency=res)
+    assert len(rec) == 64
     print("1b: n_load mean per step", [round(r["n_load_mean"], 2) for r in rec], flush=True)
+
+
+def test_1b_shaped_half_resident_one_stream_single_entry():
+    """The same workload in the order bench.py times: everything on one stream."""
+    w = CONFIGS["1b"]
+    res = random_residency(w, seed=1, layer=0, n_blocks=w.context // w.block_size)
+    run_parity(w, seed=1, steps=16, residency=res, overlap=False)
 
 
 def test_1b_overlap_and_serial_orders_agree():
@@ -91,6 +99,26 @@ def test_long_generation_growing_context():
     r = run_growing(w, seed=0, steps=200)
     print("longgen: worst err", r["worst"], "n_load max at block boundaries", r["boundary_loads"], flush=True)
     assert len(r["boundary_loads"]) == 4 and max(r["boundary_loads"][1:]) <= w.kq_blocks   # step 0 (cold) + 3 boundaries
+
+
+def test_long_generation_full_length():
+    """The whole long-generation run: prompt 4096, then all 16384 generated tokens (N grows from 64 to 320
+    blocks over 256 block boundaries), batch cut to 4 (32 units).  Token counts, Gamma, miss counts, load lists and
+    both maps are compared with the oracle at every one of the 16385 steps and n_load <= Kq is asserted
+    throughout; pooled arrays and attention outputs at steps 0-8, around each of the first 8 block
+    boundaries, at 64 seeded random steps and at the last 16; host pool, GPU pool and pooled arrays at the end."""
+    from pipeline import run_growing
+    w = CONFIGS["longgen"].replace(batch=4)
+    steps = w.generated + 1
+    att = set(range(9)) | set(range(steps - 16, steps))
+    for k in range(1, 9):                                    # token that opens block 64 + k - 1 is step 64 k
+        att |= {64 * k - 1, 64 * k, 64 * k + 1}
+    att |= set(np.random.default_rng(2024).integers(9, steps - 16, 64).tolist())
+    r = run_growing(w, seed=0, steps=steps, attention_steps=att, progress=1024)
+    print("longgen full: worst err", r["worst"], "attention checks", r["checked"], "boundaries", len(r["boundary_loads"]),
+          "max n_load at a boundary", max(r["boundary_loads"][1:]), flush=True)
+    assert len(r["boundary_loads"]) == 257 and max(r["boundary_loads"][1:]) <= w.kq_blocks
+    assert r["checked"] == len(att)
 
 
 def test_growing_context_small_ragged_fp32():
