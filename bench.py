@@ -42,6 +42,16 @@ def parse_args():
     ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--kq", type=int, default=0, help="override the query-aware budget Kq (blocks); Ke shrinks accordingly")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--slots", type=int, default=0,
+                    help="GPU pool slots C per unit (default: the workload's, C = K for the 8B shape); C > K keeps blocks beyond the selection resident")
+    ap.add_argument("--victim-policy", type=int, default=-1, choices=[-1, 0, 1],
+                    help="which free slot a missed block overwrites: 0 lowest slot, 1 least important block (default: the workload's)")
+    ap.add_argument("--no-fused-select", action="store_true",
+                    help="run block score and selection as two kernels inside nosa_decode_step (default: one kernel, scores stay on chip)")
+    ap.add_argument("--no-larger-pool", action="store_true",
+                    help="skip the second measurement of the headline workload with C = 96 slots and importance-ranked victims")
+    ap.add_argument("--locality-steps", type=int, default=64, help="untimed steps after the timed regions that record the miss count of every step")
     ap.add_argument("--study", default="", choices=["", "transfer", "prefill"],
                     help="transfer: block-wise versus element-wise host-to-device gather over miss fractions (prints one JSON line per point); "
                          "prefill: sparse prefill of one chunk at the end of the 8B-shaped context (one JSON line)")
@@ -99,15 +109,26 @@ def cpu_baseline(w, host, queries, sample_batch, seconds):
         oracle.attention(p, q, pk, pv, pb, sel, n_sel, sob, n_tok)
 
     one(0)                                   # cold start (fills the pool), untimed
-    steps, t0 = 0, time.perf_counter()
-    while steps < 2 or time.perf_counter() - t0 < seconds:
-        steps += 1
-        one(steps)
-    dt = time.perf_counter() - t0
-    return {"value": ws.units * steps / dt, "unit": "unit-steps/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{steps} whole steps (score, select, load, fetch, attention) of {ws.units} units = batch "
-                      f"{sample_batch} of {w.batch} of the {w.name}-shaped workload, same tensors as the GPU run, "
-                      f"fp64, OpenMP over units, {dt:.1f} s"}
+    threads = oracle.num_threads()
+
+    def timed(budget, first):
+        n, t0 = 0, time.perf_counter()
+        while n < 2 or time.perf_counter() - t0 < budget:
+            n += 1
+            one(first + n)
+        return n, time.perf_counter() - t0
+
+    # one thread first (a quarter of the budget), then every thread the oracle's OpenMP runtime gives it
+    oracle.set_threads(1)
+    n1, dt1 = timed(0.25 * seconds, 0)
+    oracle.set_threads(threads)
+    steps, dt = timed(0.75 * seconds, n1)
+    what = (f"whole steps (score, select, load, fetch, attention) of {ws.units} units = batch {sample_batch} of {w.batch} "
+            f"of the {w.name}-shaped workload, same tensors as the GPU run, fp64")
+    return {"value": ws.units * steps / dt, "unit": "unit-steps/s", "cores": threads, "kind": "oracle",
+            "sample": f"{steps} {what}, OpenMP over units on {threads} threads, {dt:.1f} s",
+            "single_thread": {"value": ws.units * n1 / dt1, "unit": "unit-steps/s", "cores": 1,
+                              "sample": f"{n1} {what}, one thread, {dt1:.1f} s"}}
 
 
 def transfer_study(args):
@@ -402,6 +423,34 @@ def main():
     w = CONFIGS[args.workload]
     if args.kq:
         w = w.replace(kq_blocks=args.kq)
+    if args.slots:
+        w = w.replace(gpu_slots=args.slots)
+    if args.victim_policy >= 0:
+        w = w.replace(victim_policy=args.victim_policy)
+    if args.batch:
+        w = w.replace(batch=args.batch)
+    line = measure(args, w)
+    headline = (args.workload == "8b" and not args.kq and not args.slots and args.victim_policy < 0 and not args.resident
+                and not args.batch)
+    if headline and not args.no_larger_pool:
+        # The same workload with half as many slots again per unit and importance-ranked victims: the paper's
+        # pool holds exactly the selection (C = K, the headline above); a larger pool keeps recently used
+        # blocks, the misses all but vanish and the step is bound by HBM instead of the host link.
+        a2 = argparse.Namespace(**vars(args))
+        a2.layers, a2.warmup, a2.no_cpu_baseline, a2.no_overlap = 8, max(args.warmup, 8 * 48), True, True
+        sub = measure(a2, w.replace(gpu_slots=96, victim_policy=1))
+        line["larger_pool"] = {k: sub[k] for k in ("value", "unit", "ms_per_step", "steps", "warmup", "config", "roofline", "kernels_avg_us",
+                                                    "step_hbm_GBps", "step_roofline", "locality", "fetch")}
+    print(json.dumps(line), flush=True)
+
+
+def measure(args, w):
+    """Sets the workload up, runs the timed regions and returns the JSON line as a dict."""
+    import torch
+    import paper_2510_13602_amd as nosa
+    from nosa_inputs import CONFIGS, QueryStream, make_layer
+    from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+    dev = "cuda:0"
     L = args.layers or min(w.layers, 32)
     LH = max(1, min(args.host_layers, L))
     t_setup = time.perf_counter()
@@ -409,7 +458,7 @@ def main():
     params = nosa.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
                               k_blocks=w.k_blocks, kq_blocks=w.kq_blocks, sink_blocks=w.sink_blocks,
                               window_blocks=w.window_blocks, gpu_slots=w.gpu_slots, max_blocks=w.max_blocks,
-                              n_sub_max=w.n_sub_max, dtype=w.dtype)
+                              n_sub_max=w.n_sub_max, dtype=w.dtype, victim_policy=w.victim_policy)
     stream = torch.cuda.Stream(device=dev)          # a real stream (the NULL stream cannot be captured into a graph)
     torch.cuda.set_stream(stream)
     ctx = nosa.Nosa(params, stream=stream, device=dev)
@@ -418,6 +467,7 @@ def main():
     if args.fetch_wgs:
         ctx.set_fetch_workgroups(args.fetch_wgs)
     ctx.set_overlap(False)      # the timed region runs every kernel alone on one stream; see below
+    ctx.set_fused_select(not args.no_fused_select)
 
     # host pools: every block of the cache, pinned; drawn on the GPU (seeded) and copied out
     hosts = []
@@ -426,11 +476,25 @@ def main():
         hosts.append((pinned_like(lay["host_k"]), pinned_like(lay["host_v"]), pinned_like(lay["host_bias"])))
         del lay
         torch.cuda.empty_cache()
+    # what the runtime's own copy engine moves from one of these pinned pools (the practical ceiling of the host link)
+    link_copy_GBps = None
+    if not args.resident:
+        src = hosts[0][0].view(-1)[:1 << 29]                       # up to 1 GiB of bf16 (or 2 GiB of fp32)
+        dst = torch.empty(src.shape, dtype=src.dtype, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dst.copy_(src, non_blocking=True)
+        e0.record(stream)
+        dst.copy_(src, non_blocking=True)
+        e1.record(stream)
+        e1.synchronize()
+        link_copy_GBps = src.numel() * src.element_size() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del dst
     n_tok = torch.full((w.batch,), w.context, dtype=torch.int32)
     layers = []
     for l in range(L):
         hk, hv, hb = hosts[l % LH]
         lc = LayerCache(ctx, hk, hv, hb, n_tok)
+        lc.keep_scores = args.no_fused_select      # fused Stage 1: nobody reads the block scores, so they are not written
         if l < LH:
             lc.rebuild_pooled()
         else:                                   # same host pool -> same pooled arrays
@@ -440,7 +504,7 @@ def main():
     # queries: one stream per host pool (the planted directions belong to the pool)
     streams = [QueryStream(w, args.seed, hl, device=dev) for hl in range(LH)]
     total = args.warmup + args.steps
-    n_q = 1 if args.resident else (2 * total + 16) // L + 4
+    n_q = 1 if args.resident else (2 * total + 16 + args.locality_steps) // L + 4
     queries = [[streams[hl].next(t) for t in range(n_q)] for hl in range(LH)]
 
     def q_of(l, i):
@@ -520,16 +584,43 @@ def main():
                    "note": "gather on the side stream; sparse_decode = attention over resident blocks (runs beside the gather), "
                            "combine = attention over fetched blocks + merge"}
 
+    # locality gamma(t) = #(Gamma(t) ^ Gamma(t-1)) / #Gamma(t): with the pool holding the previous selection
+    # (and whatever else fits) the blocks NOT fetched are exactly the ones found resident, so
+    # gamma(t) >= 1 - n_load / n_sel.  An untimed pass records the miss count of every unit at every step.
+    locality = None
+    if args.locality_steps > 0 and not args.resident:
+        n_loc = args.locality_steps
+        hist = torch.zeros((n_loc, w.batch, w.n_kv_heads), dtype=torch.int32, device=dev)
+        mode = args.mode
+        if mode == "graph":
+            args.mode = "fused"
+        for i in range(n_loc):
+            j = step_no[0]
+            do_step(j % L, q_of(j % L, 1 + j))
+            hist[i].copy_(layers[j % L].n_load)
+            step_no[0] += 1
+        args.mode = mode
+        torch.cuda.synchronize()
+        hit = 1.0 - hist.float() / float(min(w.k_blocks, w.max_blocks))
+        locality = {"definition": "gamma(t) = 1 - blocks fetched / blocks selected, per unit and step",
+                    "mean": float(hit.mean().item()), "min": float(hit.min().item()),
+                    "guaranteed_when_C_equals_K": (w.k_blocks - w.kq_blocks) / w.k_blocks,
+                    "steps": n_loc, "units": w.units,
+                    "mean_blocks_fetched": float(hist.float().mean().item()), "max_blocks_fetched": int(hist.max().item())}
+
     units = w.units
     dec_us = kern["sparse_decode"]
     dec_bytes = decode_bytes_per_unit(w) * units
     achieved = dec_bytes / (dec_us * 1e-6) / 1e9 if dec_us else None
     peak = 8000.0
-    traffic = None
+    # HBM bytes per launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE): a stored measurement of this
+    # kernel on this workload, not taken during this run (counters need the profiler attached)
+    traffic, traffic_source = None, None
     tfile = os.path.join(ROOT, "profiles", f"sparse_decode_{w.name}_hbm_traffic.json")
-    if os.path.exists(tfile):
+    if os.path.exists(tfile) and w.gpu_slots == CONFIGS[w.name].gpu_slots:
         with open(tfile) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
+        traffic_source = f"profiles/sparse_decode_{w.name}_hbm_traffic.md (rocprofv3 --pmc run of this command, stored; not measured in this run)"
     blk_bytes = 2 * w.block_size * w.head_dim * w.elem_size + w.block_size * 4
     fetch_us = kern["fetch"]
     line = {
@@ -543,26 +634,44 @@ def main():
         "config": {"workload": f"{w.name}-shaped", "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "context": w.context, "block_size": w.block_size, "k_blocks": w.k_blocks,
                    "kq_blocks": w.kq_blocks, "sink_blocks": w.sink_blocks, "window_blocks": w.window_blocks,
-                   "gpu_slots": w.gpu_slots, "layers_cycled": L, "host_pools": LH, "splits": ctx.splits, "step_entry": args.mode,
+                   "gpu_slots": w.gpu_slots, "victim_policy": w.victim_policy, "layers_cycled": L,
+                   "stage1": "two kernels" if (args.no_fused_select or args.mode == "calls") else "one kernel (scores + selection + load positions)", "host_pools": LH, "splits": ctx.splits, "step_entry": args.mode,
                    "fetch": "resident (no misses)" if args.resident else "main stream (every kernel alone)"},
         "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<bf16,128,4,false>" if w.name == "8b" else "decode_partial_kernel",
                      "achieved": achieved, "peak": peak, "unit": "GB/s",
-                     "frac": (achieved / peak) if achieved else None, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": dec_bytes, "avg_launch_us": dec_us},
+                     "frac": (achieved / peak) if achieved else None, "traffic": traffic, "traffic_source": traffic_source,
+                     "algorithmic_bytes_per_launch": dec_bytes, "avg_launch_us": dec_us,
+                     "scope": "the attention kernel alone (the dominant HBM kernel); the whole step is priced in step_roofline"},
         "cpu_baseline": None,
         "kernels_avg_us": kern,
         "overlap": overlap,
         "step_hbm_GBps": step_bytes_per_unit(w) * units * args.steps / dt / 1e9,
+        "step_roofline": None,
+        "locality": locality,
         "fetch": {"mean_blocks_per_unit": mean_load, "max_blocks_per_unit": max_load, "cold_start_blocks_per_unit": cold_loads,
                   "host_link_GBps": (mean_load * units * blk_bytes / (fetch_us * 1e-6) / 1e9) if fetch_us else None},
         "setup_s": setup_s,
     }
+    # What bounds the whole step: its HBM bytes at 8 TB/s, or the bytes it pulls over the host link at the
+    # rate the runtime's own copy of pinned memory reaches on this machine.
+    step_s = dt / args.steps
+    hbm_s = step_bytes_per_unit(w) * units / 8e12
+    link_bytes = mean_load * units * blk_bytes
+    link_s = link_bytes / (link_copy_GBps * 1e9) if link_copy_GBps else 0.0
+    if link_s > hbm_s:
+        line["step_roofline"] = {"bound": "host link", "achieved": link_bytes / step_s / 1e9, "peak": link_copy_GBps, "unit": "GB/s",
+                                 "frac": link_bytes / step_s / 1e9 / link_copy_GBps, "peak_source": "pinned-to-device copy of 1 GiB by the runtime, measured in this run",
+                                 "link_bytes_per_step": link_bytes, "step_hbm_frac": line["step_hbm_GBps"] / peak}
+    else:
+        line["step_roofline"] = {"bound": "hbm", "achieved": line["step_hbm_GBps"], "peak": peak, "unit": "GB/s",
+                                 "frac": line["step_hbm_GBps"] / peak, "link_bytes_per_step": link_bytes,
+                                 "link_copy_GBps": link_copy_GBps}
     if not args.no_cpu_baseline:
         layers.clear()
         torch.cuda.empty_cache()
         line["cpu_baseline"] = cpu_baseline(w, hosts[0], queries[0], min(args.cpu_sample_batch, w.batch), args.cpu_seconds)
     ctx.close()
-    print(json.dumps(line), flush=True)
+    return line
 
 
 if __name__ == "__main__":

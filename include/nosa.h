@@ -90,7 +90,8 @@ int nosa_destroy(nosa_ctx* ctx); /* synchronises both streams, destroys them; fr
 
 /* Scratch for the split partial results of nosa_sparse_decode.  The caller allocates
  * nosa_workspace_bytes() bytes of device memory (256-byte aligned) and hands them over once; the
- * buffer must stay valid until nosa_destroy.                                                     */
+ * buffer must stay valid until nosa_destroy.  nosa_set_workspace enqueues one small kernel on the
+ * context's stream that zeroes the per-unit arrival counters at the start of the buffer.          */
 size_t nosa_workspace_bytes(const nosa_params* p);
 int nosa_set_workspace(nosa_ctx* ctx, void* dev_ws, size_t bytes);
 
@@ -99,6 +100,11 @@ int nosa_set_workspace(nosa_ctx* ctx, void* dev_ws, size_t bytes);
 #define NOSA_MAX_SPLITS 16
 int nosa_set_splits(nosa_ctx* ctx, int splits);
 int nosa_get_splits(const nosa_ctx* ctx);
+
+/* With several splits, who merges the partial results of a unit: 1 (default) the workgroup of the
+ * attention kernel that finds all the others of its unit done (an arrival counter per unit, nobody
+ * waits); 0 a separate combine launch.  Same arithmetic in the same order, same result.           */
+int nosa_set_merge_in_kernel(nosa_ctx* ctx, int on);
 
 /* overlap = 1 (default): fetches run on the context's own stream; a nosa_sparse_decode that follows
  * a nosa_fetch first attends the selected blocks that are not in that fetch's load list, then waits
@@ -171,9 +177,10 @@ int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const v
  * kernels and same result, but the split partial results live in a scratch array of
  * NOSA_STATIC_SCRATCH_BYTES that is part of the library's device code (one copy per GPU, held until the
  * process ends) instead of in the workspace of nosa_set_workspace, which need not be set.  The call
- * allocates nothing.  It needs units x splits x G x (d + 2) x 4 bytes and returns NOSA_ESHAPE when
- * that exceeds the array (lower nosa_set_splits, or use nosa_sparse_decode).  Nothing in the array
- * has to start at zero: every partial result is written before it is read.  All contexts of a process
+ * allocates nothing.  It needs units x (4 + splits x G x (d + 2) x 4) bytes (+ 256) and returns NOSA_ESHAPE when
+ * that exceeds the array (lower nosa_set_splits, or use nosa_sparse_decode).  The array starts at zero
+ * when the library is loaded and only the per-unit arrival counters at its start rely on that: every launch
+ * leaves them at zero again; partial results are written before they are read.  All contexts of a process
  * share a GPU's array and it keeps the last call's contents, so two such calls that overlap in time
  * on one GPU (different streams, or a graph replay beside an eager call) race; calls on one stream
  * are ordered.                                                                                     */
@@ -185,7 +192,13 @@ int nosa_sparse_decode_static(nosa_ctx* ctx, const void* q, const void* pool_k, 
 /* One whole decode step of one layer = the four calls above, in the order of Alg. 1, behind one
  * entry point (one boundary crossing per step instead of four).  Every field has the meaning and
  * memory kind of the like-named argument above; host_bias / pool_bias may both be NULL, lse may be
- * NULL.                                                                                           */
+ * NULL.
+ * With one pooled key per block (pool_kernel == pool_stride == block_size) and at most 1024 blocks
+ * (and slots) per unit, Stage 1 runs as ONE kernel: a workgroup per unit streams the unit's pooled
+ * keys, keeps the block scores in LDS and selects from there (same arithmetic and same results as
+ * nosa_block_score followed by nosa_select).  sq_blk and se_blk are then optional outputs: pass NULL
+ * and the scores never travel through HBM (nosa_append needs se_blk: keep it for a growing context).
+ * nosa_set_fused_select(ctx, 0) switches back to the two separate kernels.                        */
 typedef struct {
   const void* q;
   const void* k_pooled;
@@ -209,6 +222,7 @@ typedef struct {
   float* lse;
 } nosa_step_args;
 int nosa_decode_step(nosa_ctx* ctx, const nosa_step_args* args);
+int nosa_set_fused_select(nosa_ctx* ctx, int on);
 
 /* The same step recorded once into a HIP graph (Sec. 4 "Kernel Fusion": the paper captures the
  * launch-bound part of the step in a graph) and replayed with one launch.  All pointers are baked

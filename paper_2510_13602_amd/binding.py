@@ -25,8 +25,8 @@ STATIC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = [
     "nosa_validate_params", "nosa_create", "nosa_destroy", "nosa_workspace_bytes", "nosa_set_workspace",
-    "nosa_set_splits", "nosa_get_splits", "nosa_set_overlap", "nosa_set_fetch_workgroups", "nosa_last_error", "nosa_block_score",
-    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_sparse_decode_static", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_fetch_tokens", "nosa_decode_step", "nosa_graph_create", "nosa_graph_launch",
+    "nosa_set_splits", "nosa_get_splits", "nosa_set_merge_in_kernel", "nosa_set_overlap", "nosa_set_fetch_workgroups", "nosa_last_error", "nosa_block_score",
+    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_sparse_decode_static", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_fetch_tokens", "nosa_decode_step", "nosa_set_fused_select", "nosa_graph_create", "nosa_graph_launch",
     "nosa_graph_destroy", "nosa_prefill_select", "nosa_prefill_attend", "nosa_timing_enable",
     "nosa_timing_read",
 ]
@@ -75,8 +75,10 @@ def load_library() -> ctypes.CDLL:
     lib.nosa_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
     lib.nosa_set_splits.argtypes = [vp, ctypes.c_int]
     lib.nosa_get_splits.argtypes = [vp]
+    lib.nosa_set_merge_in_kernel.argtypes = [vp, ctypes.c_int]
     lib.nosa_set_overlap.argtypes = [vp, ctypes.c_int]
     lib.nosa_set_fetch_workgroups.argtypes = [vp, ctypes.c_int]
+    lib.nosa_set_fused_select.argtypes = [vp, ctypes.c_int]
     lib.nosa_last_error.argtypes = [vp]
     lib.nosa_last_error.restype = ctypes.c_char_p
     lib.nosa_block_score.argtypes = [vp, vp, vp, fp, i32p, fp, fp]
@@ -184,8 +186,14 @@ class Nosa:
     def set_splits(self, s: int) -> None:
         self._check(self.lib.nosa_set_splits(self._ctx, s))
 
+    def set_merge_in_kernel(self, on: bool) -> None:
+        self._check(self.lib.nosa_set_merge_in_kernel(self._ctx, 1 if on else 0))
+
     def set_overlap(self, on: bool) -> None:
         self._check(self.lib.nosa_set_overlap(self._ctx, 1 if on else 0))
+
+    def set_fused_select(self, on: bool) -> None:
+        self._check(self.lib.nosa_set_fused_select(self._ctx, 1 if on else 0))
 
     def set_fetch_workgroups(self, n: int) -> None:
         self._check(self.lib.nosa_set_fetch_workgroups(self._ctx, n))
@@ -341,7 +349,7 @@ class Nosa:
         return StepArgs(
             v(_dev(q, self.tdtype, (B, p.n_q_heads, d), "q")), v(_dev(k_pooled, self.tdtype, (B, H, p.n_sub_max, d), "k_pooled")),
             v(_dev(se_pooled, torch.float32, (B, H, p.n_sub_max), "se_pooled")), v(_dev(n_tokens, torch.int32, (B,), "n_tokens")),
-            v(_dev(sq_blk, torch.float32, (B, H, p.max_blocks), "sq_blk")), v(_dev(se_blk, torch.float32, (B, H, p.max_blocks), "se_blk")),
+            v(_dev(sq_blk, torch.float32, (B, H, p.max_blocks), "sq_blk")), v(_dev(se_blk, torch.float32, (B, H, p.max_blocks), "se_blk")),   # optional
             v(_dev(sel_idx, torch.int32, (B, H, p.k_blocks), "sel_idx")), v(_dev(n_sel, torch.int32, (B, H), "n_sel")),
             v(_dev(slot_of_block, torch.int32, (B, H, p.max_blocks), "slot_of_block")),
             v(_dev(block_of_slot, torch.int32, (B, H, p.gpu_slots), "block_of_slot")),

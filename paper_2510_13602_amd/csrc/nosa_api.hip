@@ -106,7 +106,8 @@ size_t nosa_workspace_bytes(const nosa_params* p) {
   const size_t g = p->n_q_heads / p->n_kv_heads;
   // two partitions (resident, fetched) x NOSA_MAX_SPLITS partial results per unit: O[g][d], (m, l)[g]
   const size_t per_part = g * (size_t)(p->head_dim + 2) * sizeof(float);
-  return units * 2 * NOSA_MAX_SPLITS * per_part + 256;
+  const size_t counters = ((units * sizeof(int32_t)) + 255) & ~(size_t)255;   // one arrival counter per unit
+  return counters + units * 2 * NOSA_MAX_SPLITS * per_part + 256;
 }
 
 int nosa_create(nosa_ctx** out, const nosa_params* p, void* main_stream) {
@@ -180,6 +181,12 @@ int nosa_set_workspace(nosa_ctx* ctx, void* dev_ws, size_t bytes) {
                nosa_workspace_bytes(&ctx->p));
   ctx->ws = dev_ws;
   ctx->ws_bytes = bytes;
+  return nosa::decode_zero_counters(ctx, dev_ws);
+}
+
+int nosa_set_merge_in_kernel(nosa_ctx* ctx, int on) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  ctx->merge_in_kernel = on ? 1 : 0;
   return NOSA_OK;
 }
 
@@ -196,6 +203,12 @@ int nosa_set_fetch_workgroups(nosa_ctx* ctx, int workgroups) {
   NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
   NOSA_REQUIRE(ctx, workgroups >= 1 && workgroups <= 65535, NOSA_EINVAL, "workgroups %d not in [1, 65535]", workgroups);
   ctx->fetch_wgs = workgroups;
+  return NOSA_OK;
+}
+
+int nosa_set_fused_select(nosa_ctx* ctx, int on) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  ctx->fuse_stage1 = on ? 1 : 0;
   return NOSA_OK;
 }
 
@@ -387,12 +400,39 @@ int nosa_sparse_decode_static(nosa_ctx* ctx, const void* q, const void* pool_k, 
                        ctx->static_scratch);
 }
 
+// Stage 1 of the step in one launch: scores stay on chip between the score and the selection.
+static int score_select(nosa_ctx* ctx, const nosa_step_args* a) {
+  NOSA_REQUIRE(ctx, a->q && a->n_tokens && a->sel_idx && a->n_sel && a->slot_of_block && a->block_of_slot && a->load_list &&
+                        a->n_load,
+               NOSA_EINVAL, "nosa_decode_step: NULL argument");
+  NOSA_REQUIRE(ctx, ctx->p.n_sub_max == 0 || (a->k_pooled && a->se_pooled), NOSA_EINVAL,
+               "nosa_decode_step: k_pooled / se_pooled is NULL");
+  if (ctx->fetch_pending) {   // the maps and the slots may still be in use by the previous step's fetch
+    NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, ctx->ev_fetch, 0));
+    ctx->fetch_pending = false;
+  }
+  int rc = nosa::launch_score_select(ctx, a->q, a->k_pooled, a->se_pooled, a->n_tokens, a->sq_blk, a->se_blk, a->sel_idx,
+                                     a->n_sel, a->slot_of_block, a->block_of_slot, a->load_list, a->n_load);
+  if (rc != NOSA_OK) return rc;
+  NOSA_HIP(ctx, hipEventRecord(ctx->ev_select, ctx->main));
+  ctx->select_recorded = true;
+  return NOSA_OK;
+}
+
 static int run_step(nosa_ctx* ctx, const nosa_step_args* a) {
-  int rc = nosa_block_score(ctx, a->q, a->k_pooled, a->se_pooled, a->n_tokens, a->sq_blk, a->se_blk);
-  if (rc != NOSA_OK) return rc;
-  rc = nosa_select(ctx, a->sq_blk, a->se_blk, a->n_tokens, a->sel_idx, a->n_sel, a->slot_of_block, a->block_of_slot,
-                   a->load_list, a->n_load);
-  if (rc != NOSA_OK) return rc;
+  int rc;
+  if (ctx->fuse_stage1 && nosa::score_select_supported(ctx->p)) {
+    rc = score_select(ctx, a);
+    if (rc != NOSA_OK) return rc;
+  } else {
+    NOSA_REQUIRE(ctx, a->sq_blk && a->se_blk, NOSA_EINVAL,
+                 "nosa_decode_step: sq_blk / se_blk may only be NULL when scores and selection run as one kernel");
+    rc = nosa_block_score(ctx, a->q, a->k_pooled, a->se_pooled, a->n_tokens, a->sq_blk, a->se_blk);
+    if (rc != NOSA_OK) return rc;
+    rc = nosa_select(ctx, a->sq_blk, a->se_blk, a->n_tokens, a->sel_idx, a->n_sel, a->slot_of_block, a->block_of_slot,
+                     a->load_list, a->n_load);
+    if (rc != NOSA_OK) return rc;
+  }
   rc = nosa_fetch(ctx, a->host_k, a->host_v, a->host_bias, a->pool_k, a->pool_v, a->pool_bias, a->load_list, a->n_load);
   if (rc != NOSA_OK) return rc;
   return nosa_sparse_decode(ctx, a->q, a->pool_k, a->pool_v, a->pool_bias, a->sel_idx, a->n_sel, a->slot_of_block,

@@ -59,6 +59,7 @@ struct DecodeArgs {
   const int32_t* n_tokens;
   float* part_o;   // [units][splits][G][D] un-normalised
   float* part_ml;  // [units][splits][G][2]  (m in log2 domain, l)
+  int32_t* arrived;   // [units] workgroups of a unit that have written their partial result (zero between launches)
   void* out;
   float* lse;
   const int32_t* load_list;   // phases 1 and 2: the (block, slot) pairs of the fetch in flight
@@ -130,6 +131,99 @@ __device__ __forceinline__ void store_out(void* out, size_t idx, float v, int dt
       u >>= 16;
     }
     ((uint16_t*)out)[idx] = (uint16_t)u;
+  }
+}
+
+// Partial results that are exchanged between workgroups of ONE launch travel as relaxed device-scope
+// atomics: such stores are written through the XCD's L2 and such loads do not hit lines that another
+// XCD may have made stale, so the data is coherent across the chip's eight L2 caches without the
+// whole-cache write-back and invalidate that a device-scope fence costs (measured: those fences, one per
+// workgroup, tripled the kernel's duration).  Ordering is then a matter of waiting for the stores to be
+// acknowledged before the arrival counter is bumped.
+template <bool COHERENT>
+__device__ __forceinline__ float part_load(const float* p) {
+  if constexpr (COHERENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else return *p;
+}
+template <bool COHERENT>
+__device__ __forceinline__ void part_store(float* p, float v) {
+  if constexpr (COHERENT) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
+}
+__device__ __forceinline__ void wait_vector_memory() {   // s_waitcnt vmcnt(0): this wave's loads and stores are done
+  __builtin_amdgcn_s_waitcnt(0 | (0x7 << 4) | (0xf << 8));
+}
+
+// Log-sum-exp merge of the `splits` partial results of one unit into the output, by one workgroup.
+// Used by the stand-alone combine kernel (COHERENT = false: a kernel boundary lies between writers and
+// reader) and by the last workgroup of a unit inside the attention kernel (COHERENT = true): the same
+// arithmetic in the same order, so both give the same bits.
+template <int DT, bool COHERENT>
+__device__ __forceinline__ void combine_unit(const float* part_o, const float* part_ml, void* out, float* lse, int unit,
+                                             int n_kv_heads, int G, int D, int splits) {
+  const int b = unit / n_kv_heads, h = unit % n_kv_heads;
+  for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+    const int g = idx / D, e = idx % D;
+    const size_t p0 = ((size_t)unit * splits) * G + g;
+    float M = -INFINITY;
+    for (int s = 0; s < splits; ++s) M = fmaxf(M, part_load<COHERENT>(part_ml + (p0 + (size_t)s * G) * 2));
+    float L = 0.f, O = 0.f;
+    for (int s = 0; s < splits; ++s) {
+      const size_t pi = p0 + (size_t)s * G;
+      const float ms = part_load<COHERENT>(part_ml + pi * 2);
+      const float sc = (ms == -INFINITY) ? 0.f : fast_exp2(ms - M);
+      L = fmaf(part_load<COHERENT>(part_ml + pi * 2 + 1), sc, L);
+      O = fmaf(part_load<COHERENT>(part_o + pi * D + e), sc, O);
+    }
+    const size_t o = ((size_t)b * n_kv_heads * G + (size_t)h * G + g) * D + e;
+    store_out(out, o, L > 0.f ? O / L : 0.f, DT);
+    if (lse && e == 0) lse[(size_t)b * n_kv_heads * G + h * G + g] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
+  }
+}
+
+// The merge as done by the last workgroup of a unit inside the attention kernel: the arithmetic of
+// combine_unit in the same order (so the same bits), but every partial value a lane needs -- up to SMAX
+// splits for each of its output elements -- is requested before the first one is used, so the merge pays
+// one round trip to memory instead of one per split.  Splits beyond `splits` contribute m = -inf, l = 0:
+// a term of weight zero.
+template <int DT, int D, int G, int SMAX>
+__device__ __forceinline__ void merge_arrived(const float* part_o, const float* part_ml, void* out, float* lse, int unit,
+                                              int n_kv_heads, int splits) {
+  constexpr int NI = (G * D + kThreads - 1) / kThreads;
+  const int b = unit / n_kv_heads, h = unit % n_kv_heads;
+  float ms[NI][SMAX], ls[NI][SMAX], os[NI][SMAX];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int idx = threadIdx.x + i * kThreads;
+    const bool ok = idx < G * D;
+    const int g = ok ? idx / D : 0, e = idx % D;
+#pragma unroll
+    for (int s = 0; s < SMAX; ++s) {
+      const bool live = ok && s < splits;
+      const size_t pi = ((size_t)unit * splits + (live ? s : 0)) * G + g;
+      ms[i][s] = live ? part_load<true>(part_ml + pi * 2) : -INFINITY;
+      ls[i][s] = live ? part_load<true>(part_ml + pi * 2 + 1) : 0.f;
+      os[i][s] = live ? part_load<true>(part_o + pi * D + e) : 0.f;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int idx = threadIdx.x + i * kThreads;
+    if (idx >= G * D) continue;
+    const int g = idx / D, e = idx % D;
+    float M = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < SMAX; ++s) M = fmaxf(M, ms[i][s]);
+    float L = 0.f, O = 0.f;
+#pragma unroll
+    for (int s = 0; s < SMAX; ++s) {
+      const float sc = (ms[i][s] == -INFINITY) ? 0.f : fast_exp2(ms[i][s] - M);
+      L = fmaf(ls[i][s], sc, L);
+      O = fmaf(os[i][s], sc, O);
+    }
+    const size_t o = ((size_t)b * n_kv_heads * G + (size_t)h * G + g) * D + e;
+    store_out(out, o, L > 0.f ? O / L : 0.f, DT);
+    if (lse && e == 0) lse[(size_t)b * n_kv_heads * G + h * G + g] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
   }
 }
 
@@ -295,37 +389,54 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
       }
     }
 
+    // New running maxima.  When no lane of the wave sees one move (the usual case once a few tiles have
+    // passed), every rescale factor is exactly 1 and the multiplications are skipped: same bits, fewer
+    // instructions.
+    float m_new[G];
+    bool moved = false;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float mt = s[g][0];
 #pragma unroll
       for (int i = 1; i < STEPS; ++i) mt = fmaxf(mt, s[g][i]);
-      const float m_new = fmaxf(m[g], mt);
-      const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
-      const float alpha = fast_exp2(m[g] - m_use);
-      m[g] = m_new;
-      l[g] *= alpha;
+      m_new[g] = fmaxf(m[g], mt);
+      moved |= m_new[g] != m[g];
+    }
+    if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {
 #pragma unroll
-      for (int e = 0; e < LE; ++e) acc[g][e] *= alpha;
+      for (int g = 0; g < G; ++g) {
+        const float m_use = (m_new[g] == NEG_INF) ? 0.f : m_new[g];
+        const float alpha = fast_exp2(m[g] - m_use);
+        m[g] = m_new[g];
+        l[g] *= alpha;
+#pragma unroll
+        for (int e = 0; e < LE; ++e) acc[g][e] *= alpha;
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float m_use = (m[g] == NEG_INF) ? 0.f : m[g];
 #pragma unroll
       for (int i = 0; i < STEPS; ++i) s[g][i] = fast_exp2(s[g][i] - m_use);
     }
 #pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
+    for (int i = 0; i < STEPS; ++i)
 #pragma unroll
       for (int g = 0; g < G; ++g) l[g] += s[g][i];
 #pragma unroll
-      for (int v = 0; v < VPL; ++v) {
-        float vf[EPL];
-        vx[i][v].widen(vf);
+      for (int i = 0; i < STEPS; ++i) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-          const float p = s[g][i];
+        for (int v = 0; v < VPL; ++v) {
+          float vf[EPL];
+          vx[i][v].widen(vf);
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) acc[g][v * EPL + e] = fmaf(p, vf[e], acc[g][v * EPL + e]);
+          for (int g = 0; g < G; ++g) {
+            const float p = s[g][i];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[g][v * EPL + e] = fmaf(p, vf[e], acc[g][v * EPL + e]);
+          }
         }
       }
-    }
   }
 
   // ---- merge the 8 row-group states of this wave (lane exchange) ----
@@ -399,10 +510,44 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
       if (a.lse && e == 0) a.lse[(size_t)b * a.n_kv_heads * G + h * G + g] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : NEG_INF;
     } else {
       const size_t pidx = ((size_t)unit * a.splits + split) * G + g;
-      a.part_o[pidx * D + e] = O;
-      if (e == 0) {
-        a.part_ml[pidx * 2] = M;
-        a.part_ml[pidx * 2 + 1] = L;
+      if (!OVERLAP && a.arrived) {       // read by another workgroup of this very launch
+        part_store<true>(a.part_o + pidx * D + e, O);
+        if (e == 0) {
+          part_store<true>(a.part_ml + pidx * 2, M);
+          part_store<true>(a.part_ml + pidx * 2 + 1, L);
+        }
+      } else {
+        a.part_o[pidx * D + e] = O;
+        if (e == 0) {
+          a.part_ml[pidx * 2] = M;
+          a.part_ml[pidx * 2 + 1] = L;
+        }
+      }
+    }
+  }
+  if constexpr (!OVERLAP) {
+    // Several splits and a counter array: the workgroup that finds all the others of its unit done merges
+    // their partial results into the output, which saves the separate combine launch.  Every lane waits
+    // until its partial-result stores are acknowledged, the workgroup meets, one lane bumps the unit's
+    // counter; whoever reads splits - 1 there is the last arrival and does the merge.  Nobody waits for
+    // anybody else.  The last arrival puts the counter back to zero for the next launch.
+    if (a.splits > 1 && a.arrived != nullptr) {
+      __shared__ int s_last;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      wait_vector_memory();
+      __syncthreads();
+      if (tid == 0) {
+        const int before = __hip_atomic_fetch_add(a.arrived + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = before == a.splits - 1;
+      }
+      __syncthreads();
+      if (s_last) {
+        wait_vector_memory();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        if (a.splits <= 4) merge_arrived<DT, D, G, 4>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, a.splits);
+        else if (a.splits <= 8) merge_arrived<DT, D, G, 8>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, a.splits);
+        else combine_unit<DT, true>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, G, D, a.splits);
+        if (tid == 0) __hip_atomic_store(a.arrived + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
   }
@@ -413,25 +558,7 @@ template <int DT>
 __global__ __launch_bounds__(kThreads) void decode_combine_kernel(const float* __restrict__ part_o,
                                                                   const float* __restrict__ part_ml, void* out,
                                                                   float* lse, int n_kv_heads, int G, int D, int splits) {
-  const int unit = blockIdx.x;
-  const int b = unit / n_kv_heads, h = unit % n_kv_heads;
-  for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
-    const int g = idx / D, e = idx % D;
-    const size_t p0 = ((size_t)unit * splits) * G + g;
-    float M = -INFINITY;
-    for (int s = 0; s < splits; ++s) M = fmaxf(M, part_ml[(p0 + (size_t)s * G) * 2]);
-    float L = 0.f, O = 0.f;
-    for (int s = 0; s < splits; ++s) {
-      const size_t pi = p0 + (size_t)s * G;
-      const float ms = part_ml[pi * 2];
-      const float sc = (ms == -INFINITY) ? 0.f : fast_exp2(ms - M);
-      L = fmaf(part_ml[pi * 2 + 1], sc, L);
-      O = fmaf(part_o[pi * D + e], sc, O);
-    }
-    const size_t o = ((size_t)b * n_kv_heads * G + (size_t)h * G + g) * D + e;
-    store_out(out, o, L > 0.f ? O / L : 0.f, DT);
-    if (lse && e == 0) lse[(size_t)b * n_kv_heads * G + h * G + g] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
-  }
+  combine_unit<DT, false>(part_o, part_ml, out, lse, blockIdx.x, n_kv_heads, G, D, splits);
 }
 
 template <int DT, int D, bool OVERLAP>
@@ -477,9 +604,28 @@ int decode_static_scratch(nosa_ctx* ctx, int device, void** out) {
   return NOSA_OK;
 }
 
-// Bytes of split partial results one decode call keeps in its scratch: O[G][D] and (m, l)[G] per (unit, split).
+// The scratch of a decode call starts with one arrival counter per unit (rounded up to 256 bytes) ...
+size_t decode_counter_bytes(const nosa_ctx* ctx) { return (((size_t)ctx->units * sizeof(int32_t)) + 255) & ~(size_t)255; }
+
+// ... followed by the split partial results: O[G][D] and (m, l)[G] per (unit, split).
 size_t decode_partial_bytes(const nosa_ctx* ctx) {
-  return (size_t)ctx->units * ctx->splits * ctx->group * (size_t)(ctx->p.head_dim + 2) * sizeof(float);
+  return decode_counter_bytes(ctx) +
+         (size_t)ctx->units * ctx->splits * ctx->group * (size_t)(ctx->p.head_dim + 2) * sizeof(float);
+}
+
+namespace {
+__global__ void zero_counters_kernel(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+}  // namespace
+
+// Arrival counters of a workspace the caller has just handed over must start at zero (a fill kernel, not a
+// memset, so that the call may also sit inside a stream capture).
+int decode_zero_counters(nosa_ctx* ctx, void* ws) {
+  hipLaunchKernelGGL(zero_counters_kernel, dim3((ctx->units + 255) / 256), dim3(256), 0, ctx->main, (int32_t*)ws, ctx->units);
+  NOSA_HIP(ctx, hipGetLastError());
+  return NOSA_OK;
 }
 
 bool decode_supports_group(int g) {
@@ -526,7 +672,9 @@ int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* 
   DecodeArgs a;
   a.q = q; a.pool_k = pool_k; a.pool_v = pool_v; a.pool_bias = pool_bias;
   a.sel_idx = sel_idx; a.n_sel = n_sel; a.slot_of_block = slot_of_block; a.n_tokens = n_tokens;
-  a.part_o = (float*)ws;   // scratch of the split partial results: the caller's workspace or the static array
+  // scratch (the caller's workspace or the static array): [arrival counters][partial O][partial (m, l)]
+  a.arrived = ctx->merge_in_kernel ? (int32_t*)ws : nullptr;
+  a.part_o = ws ? (float*)((char*)ws + decode_counter_bytes(ctx)) : nullptr;
   a.part_ml = a.part_o ? a.part_o + (size_t)ctx->units * S * G * D : nullptr;
   a.out = out; a.lse = lse;
   a.load_list = load_list; a.n_load = n_load;
@@ -559,7 +707,7 @@ int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* 
     NOSA_REQUIRE(ctx, dispatch<false>(p, G, a, dim3(S * ctx->units), ctx->main), NOSA_ESHAPE, "GQA group %d unsupported", G);
   }
   NOSA_HIP(ctx, hipGetLastError());
-  if (S > 1) {
+  if (S > 1 && !a.arrived) {
     TimedLaunch tl(ctx, NOSA_KERNEL_COMBINE, ctx->main);
     if (p.dtype == NOSA_DTYPE_BF16)
       hipLaunchKernelGGL((decode_combine_kernel<NOSA_DTYPE_BF16>), dim3(ctx->units), dim3(kThreads), 0, ctx->main,

@@ -41,6 +41,8 @@ struct nosa_ctx {
   const int32_t* pending_load_list = nullptr;   // arguments of the fetch in flight (caller-owned, dev)
   const int32_t* pending_n_load = nullptr;
   int overlap = 1;
+  int merge_in_kernel = 1;  // split attention: the last workgroup of a unit merges (0: a separate combine launch)
+  int fuse_stage1 = 1;      // nosa_decode_step runs scores + selection as one kernel when the shape allows
   int splits = 1;
   int fetch_wgs = 512;      // workgroups of the gather kernel (capped by the number of units)
   void* ws = nullptr;
@@ -88,6 +90,10 @@ int launch_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const
                   int32_t* sel_idx, int32_t* n_sel, int32_t* slot_of_block, int32_t* block_of_slot,
                   int32_t* load_list, int32_t* n_load, int batch_mul = 1, int se_unit_div = 1,
                   int se_stride = 0);
+int launch_score_select(nosa_ctx* ctx, const void* q, const void* k_pooled, const float* se_pooled,
+                        const int32_t* n_tokens, float* sq_blk, float* se_blk, int32_t* sel_idx, int32_t* n_sel,
+                        int32_t* slot_of_block, int32_t* block_of_slot, int32_t* load_list, int32_t* n_load);
+bool score_select_supported(const nosa_params& p);
 int launch_prefill_score(nosa_ctx* ctx, const void* q_chunk, const void* k_pooled, float* sq, int p0, int lq);
 int launch_prefill_positions(nosa_ctx* ctx, int32_t* n_tok_virtual, int p0, int lq);
 int launch_prefill_attend(nosa_ctx* ctx, const void* q_chunk, const void* cache_k, const void* cache_v,
@@ -102,6 +108,8 @@ int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* 
                   hipEvent_t wait_fetch, const int32_t* load_list, const int32_t* n_load, void* ws);
 int decode_static_scratch(nosa_ctx* ctx, int device, void** out);
 size_t decode_partial_bytes(const nosa_ctx* ctx);
+size_t decode_counter_bytes(const nosa_ctx* ctx);
+int decode_zero_counters(nosa_ctx* ctx, void* ws);
 int launch_pool_blocks(nosa_ctx* ctx, const void* keys, const float* bias, const int32_t* n_tokens,
                        void* k_pooled, float* se_pooled);
 int launch_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float* b_new, void* pool_k, void* pool_v,

@@ -46,6 +46,7 @@ class LayerCache:
         self.lse = torch.empty((B, p.n_q_heads), dtype=torch.float32, device=dev)
         self._packed = None
         self._graph = None
+        self.keep_scores = True      # False: the single-entry step does not write sq_blk / se_blk (fused Stage 1 only)
 
     def rebuild_pooled(self) -> None:
         """Pooled keys and pooled importance of the whole cache (reads the host pool from the GPU)."""
@@ -97,7 +98,8 @@ class LayerCache:
         return self.decode(q)
 
     def _args(self, q: torch.Tensor):
-        return self.nosa.step_args(q, self.k_pooled, self.se_pooled, self.n_tokens, self.sq_blk, self.se_blk, self.sel_idx,
+        sq, se = (self.sq_blk, self.se_blk) if self.keep_scores else (None, None)
+        return self.nosa.step_args(q, self.k_pooled, self.se_pooled, self.n_tokens, sq, se, self.sel_idx,
                                    self.n_sel, self.slot_of_block, self.block_of_slot, self.load_list, self.n_load,
                                    self.host_k, self.host_v, self.host_bias, self.pool_k, self.pool_v, self.pool_bias,
                                    self.out, self.lse)

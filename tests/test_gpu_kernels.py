@@ -103,6 +103,46 @@ def test_sparse_decode_parity(dtype, d, Hq, Hkv, K, nfull, tail, splits, bias):
     ctx.close()
 
 
+@pytest.mark.parametrize("dtype,d,Hq,Hkv,K,nfull,tail,splits", [
+    ("bf16", 128, 12, 2, 64, 70, 17, 4), ("bf16", 128, 8, 2, 24, 40, 63, 16), ("bf16", 64, 16, 2, 32, 64, 9, 7),
+    ("fp32", 128, 8, 2, 12, 20, 33, 3), ("fp32", 64, 4, 1, 3, 2, 1, 8), ("bf16", 128, 4, 1, 9, 12, 0, 2)])
+def test_split_merge_inside_the_kernel_equals_the_combine_launch(dtype, d, Hq, Hkv, K, nfull, tail, splits):
+    """Split attention merged by the last workgroup of each unit (arrival counters, the default) against the
+    separate combine launch: same arithmetic in the same order, so the same bits; run three times in a row so
+    that the counters are seen to return to zero."""
+    T = 64 * nfull + tail
+    w = small_workload(batch=5, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, context=T, k_blocks=K, kq_blocks=1,
+                       gpu_slots=K + 3, dtype=dtype)
+    rng = np.random.default_rng(T + K + splits)
+    layer = make_layer(w, seed=19, layer=0)
+    sel, n_sel = _random_selection(w, rng, T)
+    pk, pv, pb, sob = _scattered_pool(w, layer, sel, n_sel, seed=K)
+    n_tok = np.full((w.batch,), T, np.int32)
+    td = w.torch_dtype
+    dev_args = (from_np(pk, td), from_np(pv, td), from_np(pb, torch.float32), torch.from_numpy(sel).to(DEV),
+                torch.from_numpy(n_sel).to(DEV), torch.from_numpy(sob).to(DEV), torch.from_numpy(n_tok).to(DEV))
+    ctx = nosa.Nosa(gpu_params(w), device=DEV)
+    ctx.set_splits(splits)
+    qs = QueryStream(w, 19, 0)
+    po = oracle_params(w)
+    for t in range(3):
+        q = qs.next(t)
+        res = []
+        for inside in (True, False):
+            ctx.set_merge_in_kernel(inside)
+            out = torch.full((w.batch, Hq, d), float("nan"), dtype=td, device=DEV)
+            lse = torch.full((w.batch, Hq), float("nan"), dtype=torch.float32, device=DEV)
+            ctx.nosa_sparse_decode(q.to(DEV), *dev_args, out, lse)
+            torch.cuda.synchronize()
+            res.append((to_np(out).copy(), lse.cpu().numpy().copy()))
+        assert res[0][0].tobytes() == res[1][0].tobytes(), f"call {t}: outputs differ"
+        assert res[0][1].tobytes() == res[1][1].tobytes()
+        ref, _ = oracle.attention(po, to_np(q), pk, pv, pb, sel, n_sel, sob, n_tok)
+        got = torch.from_numpy(res[0][0].view(np.int16)).view(torch.bfloat16).double().numpy() if dtype == "bf16" else res[0][0].astype(np.float64)
+        assert np.abs(got - ref).max() <= out_tol(dtype)
+    ctx.close()
+
+
 def test_sparse_decode_empty_and_single_token():
     """n_sel = 0 gives a zero output row and lse = -inf; T = 1 attends the one token."""
     w = small_workload(batch=2, n_q_heads=4, n_kv_heads=2, head_dim=64, context=1, k_blocks=4, kq_blocks=1,

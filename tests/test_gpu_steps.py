@@ -159,6 +159,76 @@ def test_single_entry_step_equals_four_calls():
     ctx.close()
 
 
+@pytest.mark.parametrize("name,over", [
+    ("1b", dict(batch=3)),                                                        # d64, group 8, C = 64 > K = 32
+    ("1b", dict(batch=2, victim_policy=1, gpu_slots=80)),                         # ranked victims, C = 80 of 128 blocks
+    ("tiny", dict(batch=2, n_q_heads=8, n_kv_heads=2)),                           # fp32
+    ("3b", dict(batch=1, context=64 * 1000 + 11, gpu_slots=70)),                  # 1001 blocks: 16 keys per lane, ragged tail
+    ("8b", dict(batch=1, context=64 * 300)),
+])
+def test_fused_stage1_equals_score_then_select(name, over):
+    """nosa_decode_step with scores + selection + load positions in ONE kernel against the separate
+    nosa_block_score and nosa_select kernels, on twin state over several steps: scores (when asked for),
+    Gamma, load lists, maps and outputs bit for bit; and with sq_blk / se_blk = NULL the rest is unchanged."""
+    from helpers import to_np
+    from nosa_inputs import QueryStream
+    w = CONFIGS[name].replace(**over)
+    ctx, a, b = _two_layers(w, 13)
+    import paper_2510_13602_amd as nosa
+    from paper_2510_13602_amd.runtime import LayerCache
+    c = LayerCache(ctx, a.host_k, a.host_v, a.host_bias, a.n_tokens.cpu())
+    c.rebuild_pooled()
+    c.keep_scores = False
+    c.sq_blk.fill_(7.0)
+    qs = QueryStream(w, 13, 0)
+    for t in range(5):
+        q = qs.next(t).to("cuda:0")
+        ctx.set_fused_select(False)
+        oa = a.step_fused(q).clone()                 # separate kernels behind the single entry
+        ctx.set_fused_select(True)
+        ob = b.step_fused(q).clone()                 # one kernel, scores written out as well
+        oc = c.step_fused(q).clone()                 # one kernel, scores stay on chip
+        torch.cuda.synchronize()
+        for x in (b, c):
+            assert (a.sel_idx == x.sel_idx).all() and (a.n_sel == x.n_sel).all(), f"step {t}: selections differ"
+            assert (a.n_load == x.n_load).all() and (a.load_list == x.load_list).all()
+            assert (a.slot_of_block == x.slot_of_block).all() and (a.block_of_slot == x.block_of_slot).all()
+        assert to_np(a.sq_blk).tobytes() == to_np(b.sq_blk).tobytes() and to_np(a.se_blk).tobytes() == to_np(b.se_blk).tobytes()
+        assert (c.sq_blk == 7.0).all()                                   # untouched
+        assert to_np(oa).tobytes() == to_np(ob).tobytes() == to_np(oc).tobytes()
+    ctx.close()
+
+
+def test_fused_stage1_degenerate_token_counts():
+    """Empty caches, a single token, exactly one block, the table's capacity -- per batch element -- through
+    the fused kernel against the separate kernels."""
+    import paper_2510_13602_amd as nosa
+    from helpers import gpu_params
+    from nosa_inputs import QueryStream, make_layer
+    from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+    tokens = [0, 1, 64, 65, 700, 768]
+    w = CONFIGS["tiny"].replace(batch=len(tokens), n_q_heads=8, n_kv_heads=2, context=768, k_blocks=6, kq_blocks=2,
+                                sink_blocks=1, window_blocks=1, gpu_slots=7, dtype="bf16", head_dim=128)
+    layer = make_layer(w, 12, 0)
+    ctx = nosa.Nosa(gpu_params(w))
+    hk, hv, hb = pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"])
+    n_tok = torch.tensor(tokens, dtype=torch.int32)
+    a, b = LayerCache(ctx, hk, hv, hb, n_tok), LayerCache(ctx, hk, hv, hb, n_tok)
+    a.rebuild_pooled(); b.rebuild_pooled()
+    qs = QueryStream(w, 12, 0)
+    for t in range(3):
+        q = qs.next(t).to("cuda:0")
+        ctx.set_fused_select(False)
+        oa = a.step_fused(q).clone()
+        ctx.set_fused_select(True)
+        ob = b.step_fused(q).clone()
+        torch.cuda.synchronize()
+        assert (a.sel_idx == b.sel_idx).all() and (a.n_sel == b.n_sel).all() and (a.load_list == b.load_list).all()
+        assert (a.sq_blk == b.sq_blk).all() and (a.se_blk == b.se_blk).all()
+        assert (oa == ob).all()
+    ctx.close()
+
+
 def test_graph_replays_match_eager_steps():
     """The step recorded into a HIP graph, replayed 8 times with the program's own eager work and
     synchronisations between the replays; every replay must equal the eager step on twin state."""
