@@ -47,6 +47,7 @@ def parse_args():
                     help="GPU pool slots C per unit (default: the workload's, C = K for the 8B shape); C > K keeps blocks beyond the selection resident")
     ap.add_argument("--victim-policy", type=int, default=-1, choices=[-1, 0, 1],
                     help="which free slot a missed block overwrites: 0 lowest slot, 1 least important block (default: the workload's)")
+    ap.add_argument("--gen-tokens", type=int, default=16384, help="long-generation workload: tokens generated per layer state")
     ap.add_argument("--no-fused-select", action="store_true",
                     help="run block score and selection as two kernels inside nosa_decode_step (default: one kernel, scores stay on chip)")
     ap.add_argument("--no-larger-pool", action="store_true",
@@ -197,16 +198,19 @@ def transfer_study(args):
 
 
 def longgen_bench(args):
-    """Long-generation 8B-shaped workload: prompt 4096, then one token per step is produced upstream
-    (QKV split + eviction head), appended (host pool, GPU slot, pooled arrays) and attended.  A step is
-    split_qkv_evict -> append -> score -> select -> fetch -> attention of one layer; two layer states cycle."""
+    """Long-generation 8B-shaped workload: prompt 4096, then ``--gen-tokens`` tokens (default: all 16384) are
+    generated per layer state.  A step is split_qkv_evict -> append (host pool, GPU slot, pooled arrays) ->
+    score + select -> fetch -> attention of one layer; ``--layers`` layer states (default 2) take turns.
+    With ``--mode graph`` the whole step is one HIP graph replay per layer.  Three windows of 256 steps per
+    layer -- at the start (N = 64 blocks), in the middle and at the end (N = 320 at full length) -- are timed on
+    their own, with per-kernel HIP-event durations when the step is not a graph."""
     import torch
     import paper_2510_13602_amd as nosa
     from nosa_inputs import CONFIGS, QueryStream, append_token, make_layer
     from paper_2510_13602_amd.runtime import LayerCache, pinned_like
     dev = "cuda:0"
-    total = args.warmup + args.steps
-    w = CONFIGS["longgen"].replace(generated=total + 1)
+    gen = args.gen_tokens
+    w = CONFIGS["longgen"].replace(generated=gen)
     L = args.layers or 2
     stream = torch.cuda.Stream(device=dev)
     torch.cuda.set_stream(stream)
@@ -215,6 +219,7 @@ def longgen_bench(args):
                               window_blocks=w.window_blocks, gpu_slots=w.gpu_slots, max_blocks=w.max_blocks,
                               n_sub_max=w.n_sub_max, dtype=w.dtype)
     ctx = nosa.Nosa(params, stream=stream, device=dev)
+    ctx.set_fused_select(not args.no_fused_select)
     layers, streams = [], []
     for l in range(L):
         lay = make_layer(w, args.seed, l, device=dev)
@@ -229,54 +234,91 @@ def longgen_bench(args):
     w1 = (torch.randn((d, H), generator=g, device=dev) / d ** 0.5).float()
     w2 = torch.randn((H,), generator=g, device=dev).float()
     # fused activations of every step: drifting queries | appended keys | appended values
-    n_rounds = (total + L - 1) // L + 1
-    qkv = [[None] * n_rounds for _ in range(L)]
+    qkv = [torch.empty((gen + 1, B, (Hq + 2 * H) * d), dtype=w.torch_dtype, device=dev) for _ in range(L)]
     for l in range(L):
-        for t in range(n_rounds):
+        for t in range(gen + 1):
             tok = append_token(w, args.seed, l, t + 1, device=dev)
-            qkv[l][t] = torch.cat([streams[l].next(t).reshape(B, Hq * d), tok["k_new"].reshape(B, H * d),
-                                   tok["v_new"].reshape(B, H * d)], dim=1).contiguous()
+            qkv[l][t, :, :Hq * d] = streams[l].next(t).reshape(B, Hq * d)
+            qkv[l][t, :, Hq * d:(Hq + H) * d] = tok["k_new"].reshape(B, H * d)
+            qkv[l][t, :, (Hq + H) * d:] = tok["v_new"].reshape(B, H * d)
     td = w.torch_dtype
     q_out = [torch.empty((B, Hq, d), dtype=td, device=dev) for _ in range(L)]
-    k_new = torch.empty((B, H, d), dtype=td, device=dev)
-    v_new = torch.empty((B, H, d), dtype=td, device=dev)
-    b_new = torch.empty((B, H), dtype=torch.float32, device=dev)
+    k_new = [torch.empty((B, H, d), dtype=td, device=dev) for _ in range(L)]
+    v_new = [torch.empty((B, H, d), dtype=td, device=dev) for _ in range(L)]
+    b_new = [torch.empty((B, H), dtype=torch.float32, device=dev) for _ in range(L)]
+    qkv_static = [torch.empty((B, (Hq + 2 * H) * d), dtype=td, device=dev) for _ in range(L)]
     for l, lc in enumerate(layers):                     # step 0: the prompt's last token is already cached
         lc.step_fused(qkv[l][0][:, :Hq * d].reshape(B, Hq, d).contiguous())
     torch.cuda.synchronize()
+    graph = args.mode == "graph"
+    if graph:
+        for l, lc in enumerate(layers):
+            lc.capture_generation(qkv_static[l], w1, w2, 0, q_out[l], k_new[l], v_new[l], b_new[l])
+        torch.cuda.synchronize()
 
-    def do_step(i):
-        l, t = i % L, i // L + 1
-        ctx.nosa_split_qkv_evict(qkv[l][t], w1, w2, 0, q_out[l], k_new, v_new, b_new)
-        layers[l].append(k_new, v_new, b_new)
-        layers[l].step_fused(q_out[l])
+    def do_step(l, t):                                   # token t (1-based) of layer l
+        if graph:
+            qkv_static[l].copy_(qkv[l][t])
+            layers[l].replay()
+        else:
+            ctx.nosa_split_qkv_evict(qkv[l][t], w1, w2, 0, q_out[l], k_new[l], v_new[l], b_new[l])
+            layers[l].append(k_new[l], v_new[l], b_new[l])
+            layers[l].step_fused(q_out[l])
 
-    for i in range(args.warmup):
-        do_step(i)
+    win = min(256, max(1, gen // 3))
+    starts = sorted({1, max(1, gen // 2 - win // 2), gen - win + 1})
+    windows = []
+    hist = torch.zeros((win, L, B, H), dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
-    ctx.timing_enable(True)
-    for k in range(len(nosa.KERNEL_NAMES)):
-        ctx.timing_read(k)
-    t0 = time.perf_counter()
-    for i in range(args.warmup, total):
-        do_step(i)
+    t_all = time.perf_counter()
+    t = 1
+    in_windows = 0.0
+    while t <= gen:
+        if t in starts:                                  # a window: synchronise, time it on its own, read the kernel timers
+            torch.cuda.synchronize()
+            ctx.timing_enable(not graph and not args.no_kernel_timing)
+            for k in range(len(nosa.KERNEL_NAMES)):
+                ctx.timing_read(k)
+            t0 = time.perf_counter()
+            for i in range(win):
+                for l in range(L):
+                    do_step(l, t + i)
+                    hist[i, l].copy_(layers[l].n_load)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            ctx.timing_enable(False)
+            kern = {}
+            for k, name in enumerate(nosa.KERNEL_NAMES):
+                ms, n = ctx.timing_read(k)
+                if n:
+                    kern[name] = 1e3 * ms / n
+            tokens = w.context + t + win - 1
+            windows.append({"tokens_at_end": tokens, "blocks": (tokens + w.block_size - 1) // w.block_size,
+                            "ms_per_step": 1e3 * dt / (win * L), "unit_steps_per_s": w.units * win * L / dt,
+                            "kernels_avg_us": kern or None, "mean_blocks_fetched": float(hist.float().mean().item()),
+                            "max_blocks_fetched": int(hist.max().item())})
+            t += win
+            in_windows += dt
+        else:
+            nxt = min([x for x in starts if x > t] + [gen + 1])
+            for tt in range(t, nxt):
+                for l in range(L):
+                    do_step(l, tt)
+            t = nxt
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ctx.timing_enable(False)
-    kern = {}
-    for k, name in enumerate(nosa.KERNEL_NAMES):
-        ms, n = ctx.timing_read(k)
-        kern[name] = (1e3 * ms / n) if n else None
-    loads = torch.stack([lc.n_load.float() for lc in layers])
+    dt_all = time.perf_counter() - t_all
+    steps = gen * L
     line = {
-        "metric": "sparse decode steps/sec (batch x KV heads x layer units), growing context", "value": w.units * args.steps / dt,
-        "unit": "unit-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
+        "metric": "sparse decode steps/sec (batch x KV heads x layer units), growing context", "value": w.units * steps / dt_all,
+        "unit": "unit-steps/s", "n_gpus": 1, "steps": steps, "warmup": 0, "ms_per_step": 1e3 * dt_all / steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": "long-generation 8b-shaped", "batch": B, "n_q_heads": Hq, "n_kv_heads": H, "head_dim": d,
-                   "prompt": w.context, "tokens_at_end": int(layers[0].n_tokens[0].item()), "k_blocks": w.k_blocks,
-                   "kq_blocks": w.kq_blocks, "layers_cycled": L, "upstream": "split_qkv_evict + append every step"},
-        "kernels_avg_us": kern,
-        "fetch": {"mean_blocks_per_unit": float(loads.mean().item()), "max_blocks_per_unit": float(loads.max().item())},
+                   "prompt": w.context, "generated_per_layer": gen, "tokens_at_end": int(layers[0].n_tokens[0].item()),
+                   "k_blocks": w.k_blocks, "kq_blocks": w.kq_blocks, "layers_cycled": L, "step_entry": args.mode,
+                   "upstream": "split_qkv_evict + append every step" + (", inside the graph" if graph else "")},
+        "windows": windows,
+        "note": "value covers all steps; the windows are timed between their own synchronisations (with HIP-event pairs around "
+                "every kernel unless the step is a graph replay), the steps between windows run without any timing",
     }
     ctx.close()
     print(json.dumps(line), flush=True)

@@ -232,6 +232,14 @@ int nosa_set_fused_select(nosa_ctx* ctx, int on);
  * recorded for replays.  nosa_graph_launch enqueues on the context's main stream.                 */
 typedef struct nosa_graph nosa_graph;
 int nosa_graph_create(nosa_ctx* ctx, const nosa_step_args* args, nosa_graph** out);
+/* The general form: every libnosa call made on the context between nosa_graph_begin and nosa_graph_end
+ * is recorded instead of run (stream capture of the context's main stream; the fetch stream joins and
+ * leaves the capture through the context's events), e.g. the step of a growing context,
+ * nosa_split_qkv_evict -> nosa_append -> nosa_decode_step, as one graph.  A recorded fetch must be
+ * followed by the attention call that waits for it before nosa_graph_end.  Only calls that enqueue
+ * kernels belong in between (no nosa_set_workspace, nosa_timing_read, nosa_destroy).               */
+int nosa_graph_begin(nosa_ctx* ctx);
+int nosa_graph_end(nosa_ctx* ctx, nosa_graph** out);
 int nosa_graph_launch(nosa_ctx* ctx, nosa_graph* graph);
 int nosa_graph_destroy(nosa_graph* graph);
 

@@ -26,7 +26,7 @@ STATIC_SCRATCH_BYTES = 8 << 20
 EXPORTS = [
     "nosa_validate_params", "nosa_create", "nosa_destroy", "nosa_workspace_bytes", "nosa_set_workspace",
     "nosa_set_splits", "nosa_get_splits", "nosa_set_merge_in_kernel", "nosa_set_overlap", "nosa_set_fetch_workgroups", "nosa_last_error", "nosa_block_score",
-    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_sparse_decode_static", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_fetch_tokens", "nosa_decode_step", "nosa_set_fused_select", "nosa_graph_create", "nosa_graph_launch",
+    "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_sparse_decode_static", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_fetch_tokens", "nosa_decode_step", "nosa_set_fused_select", "nosa_graph_create", "nosa_graph_begin", "nosa_graph_end", "nosa_graph_launch",
     "nosa_graph_destroy", "nosa_prefill_select", "nosa_prefill_attend", "nosa_timing_enable",
     "nosa_timing_read",
 ]
@@ -92,6 +92,8 @@ def load_library() -> ctypes.CDLL:
     lib.nosa_fetch_tokens.argtypes = [vp, vp, vp, fp, vp, vp, fp, i32p, i32p, ctypes.c_int32]
     lib.nosa_decode_step.argtypes = [vp, ctypes.POINTER(StepArgs)]
     lib.nosa_graph_create.argtypes = [vp, ctypes.POINTER(StepArgs), ctypes.POINTER(vp)]
+    lib.nosa_graph_begin.argtypes = [vp]
+    lib.nosa_graph_end.argtypes = [vp, ctypes.POINTER(vp)]
     lib.nosa_graph_launch.argtypes = [vp, vp]
     lib.nosa_graph_destroy.argtypes = [vp]
     lib.nosa_timing_enable.argtypes = [vp, ctypes.c_int]
@@ -366,6 +368,14 @@ class Nosa:
     def nosa_graph_create(self, args: StepArgs) -> ctypes.c_void_p:
         g = ctypes.c_void_p()
         self._check(self.lib.nosa_graph_create(self._ctx, ctypes.byref(args), ctypes.byref(g)))
+        return g
+
+    def nosa_graph_begin(self) -> None:
+        self._check(self.lib.nosa_graph_begin(self._ctx))
+
+    def nosa_graph_end(self) -> ctypes.c_void_p:
+        g = ctypes.c_void_p()
+        self._check(self.lib.nosa_graph_end(self._ctx, ctypes.byref(g)))
         return g
 
     def nosa_graph_launch(self, graph: ctypes.c_void_p) -> None:

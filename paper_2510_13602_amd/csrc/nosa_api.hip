@@ -450,43 +450,69 @@ struct nosa_graph {
   hipGraphExec_t exec = nullptr;
 };
 
-int nosa_graph_create(nosa_ctx* ctx, const nosa_step_args* args, nosa_graph** out) {
+int nosa_graph_begin(nosa_ctx* ctx) {
   NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
-  NOSA_REQUIRE(ctx, args && out, NOSA_EINVAL, "nosa_graph_create: NULL argument");
-  *out = nullptr;
-  NOSA_REQUIRE(ctx, ctx->main != nullptr, NOSA_EINVAL, "nosa_graph_create: the default (NULL) stream cannot be captured");
+  NOSA_REQUIRE(ctx, ctx->main != nullptr, NOSA_EINVAL, "nosa_graph_begin: the default (NULL) stream cannot be captured");
+  NOSA_REQUIRE(ctx, !ctx->capturing, NOSA_EINVAL, "nosa_graph_begin: a capture is already open on this context");
   if (ctx->fetch_pending) {   // nothing from before the capture may be waited on inside it
     NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, ctx->ev_fetch, 0));
     ctx->fetch_pending = false;
   }
-  nosa_graph* g = new (std::nothrow) nosa_graph();
-  NOSA_REQUIRE(ctx, g, NOSA_EINVAL, "out of host memory");
-  const bool timing = ctx->timing;
-  ctx->timing = false;
-  hipError_t e = hipStreamBeginCapture(ctx->main, hipStreamCaptureModeRelaxed);
-  if (e != hipSuccess) {
-    ctx->timing = timing;
-    delete g;
-    return set_error(ctx, NOSA_EHIP, "hipStreamBeginCapture failed: %s", hipGetErrorString(e));
-  }
-  const int rc = run_step(ctx, args);
-  e = hipStreamEndCapture(ctx->main, &g->graph);
-  ctx->timing = timing;
+  NOSA_HIP(ctx, hipStreamBeginCapture(ctx->main, hipStreamCaptureModeRelaxed));
+  ctx->timing_before_capture = ctx->timing;
+  ctx->timing = false;        // event pairs around kernels are not recorded into graphs
+  ctx->capturing = true;
+  return NOSA_OK;
+}
+
+int nosa_graph_end(nosa_ctx* ctx, nosa_graph** out) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, out, NOSA_EINVAL, "nosa_graph_end: out is NULL");
+  *out = nullptr;
+  NOSA_REQUIRE(ctx, ctx->capturing, NOSA_EINVAL, "nosa_graph_end without nosa_graph_begin");
+  hipGraph_t graph = nullptr;
+  const hipError_t e = hipStreamEndCapture(ctx->main, &graph);
+  ctx->capturing = false;
+  ctx->timing = ctx->timing_before_capture;
   ctx->fetch_pending = false;
-  if (rc != NOSA_OK || e != hipSuccess) {
-    if (g->graph) (void)hipGraphDestroy(g->graph);
-    delete g;
-    if (rc != NOSA_OK) return rc;
-    return set_error(ctx, NOSA_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
-  }
-  e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
   if (e != hipSuccess) {
+    if (graph) (void)hipGraphDestroy(graph);
+    return set_error(ctx, NOSA_EHIP, "hipStreamEndCapture failed: %s (a fetch without the attention call that joins it?)",
+                     hipGetErrorString(e));
+  }
+  nosa_graph* g = new (std::nothrow) nosa_graph();
+  if (!g) {
+    (void)hipGraphDestroy(graph);
+    return set_error(ctx, NOSA_EINVAL, "out of host memory");
+  }
+  g->graph = graph;
+  const hipError_t ei = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
+  if (ei != hipSuccess) {
     (void)hipGraphDestroy(g->graph);
     delete g;
-    return set_error(ctx, NOSA_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+    return set_error(ctx, NOSA_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(ei));
   }
   *out = g;
   return NOSA_OK;
+}
+
+int nosa_graph_create(nosa_ctx* ctx, const nosa_step_args* args, nosa_graph** out) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, args && out, NOSA_EINVAL, "nosa_graph_create: NULL argument");
+  *out = nullptr;
+  int rc = nosa_graph_begin(ctx);
+  if (rc != NOSA_OK) return rc;
+  rc = run_step(ctx, args);
+  if (rc != NOSA_OK) {          // close the capture, keep the step's error message
+    char keep[512];
+    memcpy(keep, ctx->err, sizeof keep);
+    nosa_graph* dropped = nullptr;
+    (void)nosa_graph_end(ctx, &dropped);
+    (void)nosa_graph_destroy(dropped);
+    memcpy(ctx->err, keep, sizeof keep);
+    return rc;
+  }
+  return nosa_graph_end(ctx, out);
 }
 
 int nosa_graph_launch(nosa_ctx* ctx, nosa_graph* graph) {

@@ -49,6 +49,8 @@ struct nosa_ctx {
   size_t ws_bytes = 0;
   void* static_scratch = nullptr;   // this device's copy of the library's static scratch array
   bool timing = false;
+  bool capturing = false;             // between nosa_graph_begin and nosa_graph_end
+  bool timing_before_capture = false;
   bool prefill_score_lds_set = false;    // dynamic-LDS limit of the prefill kernels raised (done once)
   bool prefill_attend_lds_set = false;
   const void* host_ok[3] = {nullptr, nullptr, nullptr};   // host pool pointers nosa_fetch has already vetted

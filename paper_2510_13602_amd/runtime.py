@@ -117,6 +117,22 @@ class LayerCache:
         self.release_graph()
         self._graph = self.nosa.nosa_graph_create(self._args(q_static))
 
+    def capture_generation(self, qkv_static: torch.Tensor, w1: torch.Tensor, w2: torch.Tensor, mode: int,
+                           q_out: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, b_new: torch.Tensor) -> None:
+        """Records the whole step of a growing context -- split of the fused QKV activation with the eviction
+        head, append of the token, then score / select / fetch / attention -- into one HIP graph that reads the
+        activation from ``qkv_static`` (refreshed in place before every replay)."""
+        self.release_graph()
+        args = self._args(q_out)
+        self.nosa.nosa_graph_begin()
+        try:
+            self.nosa.nosa_split_qkv_evict(qkv_static, w1, w2, mode, q_out, k_new, v_new, b_new)
+            self.append(k_new, v_new, b_new)
+            self.nosa.nosa_decode_step(args)
+        finally:
+            self._graph = self.nosa.nosa_graph_end()
+        self._keep = (args, qkv_static, w1, w2, q_out, k_new, v_new, b_new)
+
     def replay(self) -> torch.Tensor:
         self.nosa.nosa_graph_launch(self._graph)
         return self.out

@@ -263,6 +263,76 @@ def test_graph_replays_match_eager_steps():
         ctx.close()
 
 
+def test_graph_of_a_generation_step_replays_like_eager():
+    """The whole step of a growing context (QKV split + eviction head, append, score / select / fetch /
+    attention) recorded into one HIP graph and replayed 140 times -- two block boundaries, eager work and
+    synchronisations between the replays -- against the same calls made eagerly on twin state: token
+    counts, selections, load lists, maps, appended keys / values / biases, pooled arrays and outputs bit
+    for bit at every step, host pools at the end."""
+    import paper_2510_13602_amd as nosa
+    from helpers import gpu_params, to_np
+    from nosa_inputs import QueryStream, append_token, make_layer
+    from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+    w = CONFIGS["longgen"].replace(batch=2, generated=150)
+    dev = "cuda:0"
+    B, Hq, H, d = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        layer = make_layer(w, 31, 0)
+        ctx = nosa.Nosa(gpu_params(w), stream=s)
+        n_tok = torch.full((B,), w.context, dtype=torch.int32)
+        twins = []
+        for _ in range(2):                        # each twin appends into its own host pool
+            lc = LayerCache(ctx, pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"]), n_tok)
+            lc.rebuild_pooled()
+            twins.append(lc)
+        a, b = twins
+        g = torch.Generator().manual_seed(5)
+        w1 = (torch.randn((d, H), generator=g) / d ** 0.5).to(dev)
+        w2 = torch.randn((H,), generator=g).to(dev)
+        td = w.torch_dtype
+        bufs = [dict(q=torch.empty((B, Hq, d), dtype=td, device=dev), k=torch.empty((B, H, d), dtype=td, device=dev),
+                     v=torch.empty((B, H, d), dtype=td, device=dev), b=torch.empty((B, H), dtype=torch.float32, device=dev))
+                for _ in range(2)]
+        qkv_static = torch.zeros((B, (Hq + 2 * H) * d), dtype=td, device=dev)
+        qs = QueryStream(w, 31, 0)
+        q0 = qs.next(0).to(dev)
+        a.step_fused(q0)                         # step 0: the prompt's last token is already in the cache
+        b.step_fused(q0)
+        s.synchronize()
+        b.capture_generation(qkv_static, w1, w2, 0, bufs[1]["q"], bufs[1]["k"], bufs[1]["v"], bufs[1]["b"])
+        s.synchronize()
+        assert (a.n_tokens == b.n_tokens).all()           # recording launched nothing
+        scratch = torch.randn(1 << 18, device=dev)
+        for t in range(1, 141):
+            tok = append_token(w, 31, 0, t)
+            qkv = torch.cat([qs.next(t).reshape(B, Hq * d), tok["k_new"].reshape(B, H * d), tok["v_new"].reshape(B, H * d)], dim=1).to(dev)
+            ctx.nosa_split_qkv_evict(qkv, w1, w2, 0, bufs[0]["q"], bufs[0]["k"], bufs[0]["v"], bufs[0]["b"])
+            a.append(bufs[0]["k"], bufs[0]["v"], bufs[0]["b"])
+            oa = a.step_fused(bufs[0]["q"])
+            qkv_static.copy_(qkv)
+            ob = b.replay()
+            s.synchronize()
+            assert (a.n_tokens == b.n_tokens).all() and int(a.n_tokens[0]) == w.context + t, f"step {t}: token counts"
+            for key in ("q", "k", "v", "b"):
+                assert to_np(bufs[0][key]).tobytes() == to_np(bufs[1][key]).tobytes(), f"step {t}: {key} differs"
+            assert (a.sel_idx == b.sel_idx).all(), f"replay {t}: selections differ"
+            assert (a.n_load == b.n_load).all() and (a.load_list == b.load_list).all()
+            assert (a.slot_of_block == b.slot_of_block).all() and (a.block_of_slot == b.block_of_slot).all()
+            assert to_np(oa).tobytes() == to_np(ob).tobytes(), f"replay {t}: outputs differ"
+            if (w.context + t) % 64 in (0, 1, 63):
+                assert to_np(a.k_pooled).tobytes() == to_np(b.k_pooled).tobytes()
+                assert to_np(a.se_pooled).tobytes() == to_np(b.se_pooled).tobytes()
+                assert to_np(a.pool_k).tobytes() == to_np(b.pool_k).tobytes()
+            scratch = (scratch * 1.0001 + 1.0).sort().values          # unrelated eager work between replays
+            float(scratch.sum().item())
+        assert to_np(a.host_k).tobytes() == to_np(b.host_k).tobytes() and to_np(a.host_v).tobytes() == to_np(b.host_v).tobytes()
+        assert to_np(a.host_bias).tobytes() == to_np(b.host_bias).tobytes()
+        assert int(a.n_tokens[0]) == w.context + 140
+        b.release_graph()
+        ctx.close()
+
+
 def test_1b_shaped_importance_ranked_victims():
     """C = 64 slots for K = 32 selected blocks: with victim_policy 1 a miss overwrites the least important
     non-selected block instead of the first free slot.  Parity with the oracle at every step, and fewer
