@@ -211,13 +211,17 @@ def longgen_bench(args):
     dev = "cuda:0"
     gen = args.gen_tokens
     w = CONFIGS["longgen"].replace(generated=gen)
+    if args.slots:
+        w = w.replace(gpu_slots=args.slots)
+    if args.victim_policy >= 0:
+        w = w.replace(victim_policy=args.victim_policy)
     L = args.layers or 2
     stream = torch.cuda.Stream(device=dev)
     torch.cuda.set_stream(stream)
     params = nosa.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
                               k_blocks=w.k_blocks, kq_blocks=w.kq_blocks, sink_blocks=w.sink_blocks,
                               window_blocks=w.window_blocks, gpu_slots=w.gpu_slots, max_blocks=w.max_blocks,
-                              n_sub_max=w.n_sub_max, dtype=w.dtype)
+                              n_sub_max=w.n_sub_max, dtype=w.dtype, victim_policy=w.victim_policy)
     ctx = nosa.Nosa(params, stream=stream, device=dev)
     ctx.set_fused_select(not args.no_fused_select)
     layers, streams = [], []
@@ -314,7 +318,8 @@ def longgen_bench(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": "long-generation 8b-shaped", "batch": B, "n_q_heads": Hq, "n_kv_heads": H, "head_dim": d,
                    "prompt": w.context, "generated_per_layer": gen, "tokens_at_end": int(layers[0].n_tokens[0].item()),
-                   "k_blocks": w.k_blocks, "kq_blocks": w.kq_blocks, "layers_cycled": L, "step_entry": args.mode,
+                   "k_blocks": w.k_blocks, "kq_blocks": w.kq_blocks, "gpu_slots": w.gpu_slots, "victim_policy": w.victim_policy,
+                   "layers_cycled": L, "step_entry": args.mode,
                    "upstream": "split_qkv_evict + append every step" + (", inside the graph" if graph else "")},
         "windows": windows,
         "note": "value covers all steps; the windows are timed between their own synchronisations (with HIP-event pairs around "
