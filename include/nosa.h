@@ -90,8 +90,9 @@ int nosa_destroy(nosa_ctx* ctx); /* synchronises both streams, destroys them; fr
 
 /* Scratch for the split partial results of nosa_sparse_decode.  The caller allocates
  * nosa_workspace_bytes() bytes of device memory (256-byte aligned) and hands them over once; the
- * buffer must stay valid until nosa_destroy.  nosa_set_workspace enqueues one small kernel on the
- * context's stream that zeroes the per-unit arrival counters at the start of the buffer.          */
+ * buffer must stay valid until nosa_destroy and belongs to this context alone (contexts must not
+ * share one).  nosa_set_workspace enqueues one small kernel on the context's stream that zeroes the
+ * per-unit arrival counters at the start of the buffer.                                           */
 size_t nosa_workspace_bytes(const nosa_params* p);
 int nosa_set_workspace(nosa_ctx* ctx, void* dev_ws, size_t bytes);
 
@@ -177,14 +178,17 @@ int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const v
  * kernels and same result, but the split partial results live in a scratch array of
  * NOSA_STATIC_SCRATCH_BYTES that is part of the library's device code (one copy per GPU, held until the
  * process ends) instead of in the workspace of nosa_set_workspace, which need not be set.  The call
- * allocates nothing.  It needs units x (4 + splits x G x (d + 2) x 4) bytes (+ 256) and returns NOSA_ESHAPE when
- * that exceeds the array (lower nosa_set_splits, or use nosa_sparse_decode).  The array starts at zero
+ * allocates nothing.  The array holds NOSA_STATIC_SCRATCH_UNITS arrival counters (a fixed region, whatever the
+ * shape of the context) followed by the partial results, units x splits x G x (d + 2) x 4 bytes; the call
+ * returns NOSA_ESHAPE when the context has more units than that or when the partial results do not fit
+ * (lower nosa_set_splits, or use nosa_sparse_decode).  The array starts at zero
  * when the library is loaded and only the per-unit arrival counters at its start rely on that: every launch
  * leaves them at zero again; partial results are written before they are read.  All contexts of a process
  * share a GPU's array and it keeps the last call's contents, so two such calls that overlap in time
  * on one GPU (different streams, or a graph replay beside an eager call) race; calls on one stream
  * are ordered.                                                                                     */
 #define NOSA_STATIC_SCRATCH_BYTES (8u << 20)
+#define NOSA_STATIC_SCRATCH_UNITS 16384
 int nosa_sparse_decode_static(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v,
                               const float* pool_bias, const int32_t* sel_idx, const int32_t* n_sel,
                               const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse);

@@ -360,7 +360,7 @@ int nosa_fetch_tokens(nosa_ctx* ctx, const void* host_k, const void* host_v, con
 
 static int sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v, const float* pool_bias,
                          const int32_t* sel_idx, const int32_t* n_sel, const int32_t* slot_of_block,
-                         const int32_t* n_tokens, void* out, float* lse, void* ws) {
+                         const int32_t* n_tokens, void* out, float* lse, void* ws, size_t counter_bytes) {
   // A gather in flight: the blocks it is writing are the ones in its load list; everything else in
   // the selection is already in place, so that part of the attention does not wait for it.
   hipEvent_t wait = nullptr;
@@ -371,7 +371,8 @@ static int sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const
     nl = ctx->pending_n_load;
     ctx->fetch_pending = false;
   }
-  return nosa::launch_decode(ctx, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse, wait, ll, nl, ws);
+  return nosa::launch_decode(ctx, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse, wait, ll, nl, ws,
+                             counter_bytes);
 }
 
 int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v,
@@ -381,7 +382,8 @@ int nosa_sparse_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const v
   NOSA_REQUIRE(ctx, q && pool_k && pool_v && sel_idx && n_sel && slot_of_block && n_tokens && out, NOSA_EINVAL,
                "nosa_sparse_decode: NULL argument");
   NOSA_REQUIRE(ctx, ctx->splits == 1 || ctx->ws, NOSA_EINVAL, "nosa_sparse_decode: no workspace set (nosa_set_workspace)");
-  return sparse_decode(ctx, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse, ctx->ws);
+  return sparse_decode(ctx, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse, ctx->ws,
+                       nosa::decode_counter_bytes(ctx));
 }
 
 int nosa_sparse_decode_static(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v,
@@ -390,14 +392,17 @@ int nosa_sparse_decode_static(nosa_ctx* ctx, const void* q, const void* pool_k, 
   NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
   NOSA_REQUIRE(ctx, q && pool_k && pool_v && sel_idx && n_sel && slot_of_block && n_tokens && out, NOSA_EINVAL,
                "nosa_sparse_decode_static: NULL argument");
-  const size_t need = nosa::decode_partial_bytes(ctx);
+  NOSA_REQUIRE(ctx, ctx->units <= NOSA_STATIC_SCRATCH_UNITS, NOSA_ESHAPE,
+               "nosa_sparse_decode_static: %d units, the static scratch keeps arrival counters for %d", ctx->units,
+               NOSA_STATIC_SCRATCH_UNITS);
+  const size_t need = nosa::decode_static_counter_bytes() + nosa::decode_partial_bytes(ctx);
   NOSA_REQUIRE(ctx, need <= (size_t)NOSA_STATIC_SCRATCH_BYTES, NOSA_ESHAPE,
                "nosa_sparse_decode_static: %d units x %d splits x %d heads need %zu bytes of partial results, the static "
                "scratch holds %zu (use fewer splits, or nosa_sparse_decode with a workspace)",
                ctx->units, ctx->splits, ctx->group, need, (size_t)NOSA_STATIC_SCRATCH_BYTES);
   NOSA_REQUIRE(ctx, ctx->static_scratch, NOSA_EINVAL, "nosa_sparse_decode_static: the context has no static scratch");
   return sparse_decode(ctx, q, pool_k, pool_v, pool_bias, sel_idx, n_sel, slot_of_block, n_tokens, out, lse,
-                       ctx->static_scratch);
+                       ctx->static_scratch, nosa::decode_static_counter_bytes());
 }
 
 // Stage 1 of the step in one launch: scores stay on chip between the score and the selection.

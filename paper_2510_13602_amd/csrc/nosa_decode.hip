@@ -604,13 +604,18 @@ int decode_static_scratch(nosa_ctx* ctx, int device, void** out) {
   return NOSA_OK;
 }
 
-// The scratch of a decode call starts with one arrival counter per unit (rounded up to 256 bytes) ...
+// The scratch of a decode call starts with one arrival counter per unit.  In a caller's workspace, which belongs
+// to one context, the counters take units * 4 bytes rounded up to 256 ...
 size_t decode_counter_bytes(const nosa_ctx* ctx) { return (((size_t)ctx->units * sizeof(int32_t)) + 255) & ~(size_t)255; }
 
-// ... followed by the split partial results: O[G][D] and (m, l)[G] per (unit, split).
+// ... in the static array, which contexts of any shape share one after the other, they take a fixed region
+// (NOSA_STATIC_SCRATCH_UNITS counters): no context ever writes partial results where another keeps counters,
+// so the counters stay zero between launches whatever ran before.
+size_t decode_static_counter_bytes() { return (size_t)NOSA_STATIC_SCRATCH_UNITS * sizeof(int32_t); }
+
+// The counters are followed by the split partial results: O[G][D] and (m, l)[G] per (unit, split).
 size_t decode_partial_bytes(const nosa_ctx* ctx) {
-  return decode_counter_bytes(ctx) +
-         (size_t)ctx->units * ctx->splits * ctx->group * (size_t)(ctx->p.head_dim + 2) * sizeof(float);
+  return (size_t)ctx->units * ctx->splits * ctx->group * (size_t)(ctx->p.head_dim + 2) * sizeof(float);
 }
 
 namespace {
@@ -666,7 +671,7 @@ bool dispatch(const nosa_params& p, int G, const DecodeArgs& a, dim3 grid, hipSt
 int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v, const float* pool_bias,
                   const int32_t* sel_idx, const int32_t* n_sel, const int32_t* slot_of_block,
                   const int32_t* n_tokens, void* out, float* lse, hipEvent_t wait_fetch,
-                  const int32_t* load_list, const int32_t* n_load, void* ws) {
+                  const int32_t* load_list, const int32_t* n_load, void* ws, size_t counter_bytes) {
   const nosa_params& p = ctx->p;
   const int G = ctx->group, D = p.head_dim, S = ctx->splits;
   DecodeArgs a;
@@ -674,7 +679,7 @@ int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* 
   a.sel_idx = sel_idx; a.n_sel = n_sel; a.slot_of_block = slot_of_block; a.n_tokens = n_tokens;
   // scratch (the caller's workspace or the static array): [arrival counters][partial O][partial (m, l)]
   a.arrived = ctx->merge_in_kernel ? (int32_t*)ws : nullptr;
-  a.part_o = ws ? (float*)((char*)ws + decode_counter_bytes(ctx)) : nullptr;
+  a.part_o = ws ? (float*)((char*)ws + counter_bytes) : nullptr;
   a.part_ml = a.part_o ? a.part_o + (size_t)ctx->units * S * G * D : nullptr;
   a.out = out; a.lse = lse;
   a.load_list = load_list; a.n_load = n_load;

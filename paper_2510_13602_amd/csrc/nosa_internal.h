@@ -107,7 +107,9 @@ int launch_fetch(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const vo
 int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* pool_v,
                   const float* pool_bias, const int32_t* sel_idx, const int32_t* n_sel,
                   const int32_t* slot_of_block, const int32_t* n_tokens, void* out, float* lse,
-                  hipEvent_t wait_fetch, const int32_t* load_list, const int32_t* n_load, void* ws);
+                  hipEvent_t wait_fetch, const int32_t* load_list, const int32_t* n_load, void* ws,
+                  size_t counter_bytes);
+size_t decode_static_counter_bytes();
 int decode_static_scratch(nosa_ctx* ctx, int device, void** out);
 size_t decode_partial_bytes(const nosa_ctx* ctx);
 size_t decode_counter_bytes(const nosa_ctx* ctx);

@@ -72,7 +72,11 @@ def test_static_scratch_decode_two_calls_second_smaller(overlap):
     small = CONFIGS["1b"].replace(batch=1, context=64 * 40 + 17)              # 2 units, ragged tail, 5 splits
     e1 = _twin_run(big, seed=21, steps=3, overlap=overlap)
     e2 = _twin_run(small, seed=22, steps=3, overlap=overlap, splits=5)
-    print(f"static scratch (overlap={overlap}): worst err big {e1:.2e}, small {e2:.2e}", flush=True)
+    # a third call with many more units than either: its arrival counters lie where a layout that packed the
+    # partial results right behind each context's own counters would have left the earlier calls' floats
+    wide = CONFIGS["1b"].replace(batch=80)                                    # 160 units x 4 splits
+    e3 = _twin_run(wide, seed=24, steps=2, overlap=overlap)
+    print(f"static scratch (overlap={overlap}): worst err big {e1:.2e}, small {e2:.2e}, wide {e3:.2e}", flush=True)
 
 
 def test_static_scratch_fp32_group4():
@@ -93,8 +97,13 @@ def test_static_scratch_rejects_sizes_beyond_the_array():
     assert rc == nosa.binding.NOSA_ESHAPE
     msg = ctx.lib.nosa_last_error(ctx._ctx).decode()
     assert "static" in msg and str(nosa.STATIC_SCRATCH_BYTES) in msg
+    big = nosa.Nosa(gpu_params(w.replace(batch=4096)), workspace=False)      # 32768 units: more than the counter region holds
+    big.set_splits(1)
+    assert big.lib.nosa_sparse_decode_static(big._ctx, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr) == nosa.binding.NOSA_ESHAPE
+    assert "arrival counters" in big.lib.nosa_last_error(big._ctx).decode()
+    big.close()
     ctx.set_splits(1)                                                         # 1 MB: fits
-    assert 512 * 4 * 130 * 4 <= nosa.STATIC_SCRATCH_BYTES
+    assert 65536 + 512 * 4 * 130 * 4 <= nosa.STATIC_SCRATCH_BYTES
     # the workspace entry point, on the other hand, refuses to split without a workspace
     ctx.set_splits(2)
     rc = ctx.lib.nosa_sparse_decode(ctx._ctx, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr, ptr)
