@@ -47,15 +47,17 @@ def parse_args():
                     help="GPU pool slots C per unit (default: the workload's, C = K for the 8B shape); C > K keeps blocks beyond the selection resident")
     ap.add_argument("--victim-policy", type=int, default=-1, choices=[-1, 0, 1],
                     help="which free slot a missed block overwrites: 0 lowest slot, 1 least important block (default: the workload's)")
+    ap.add_argument("--xcd-shift-kib", type=int, default=0, help="xcd study: place the pools of odd layer states this many KiB further into their allocations")
     ap.add_argument("--gen-tokens", type=int, default=16384, help="long-generation workload: tokens generated per layer state")
     ap.add_argument("--no-fused-select", action="store_true",
                     help="run block score and selection as two kernels inside nosa_decode_step (default: one kernel, scores stay on chip)")
     ap.add_argument("--no-larger-pool", action="store_true",
                     help="skip the second measurement of the headline workload with C = 96 slots and importance-ranked victims")
     ap.add_argument("--locality-steps", type=int, default=64, help="untimed steps after the timed regions that record the miss count of every step")
-    ap.add_argument("--study", default="", choices=["", "transfer", "prefill"],
+    ap.add_argument("--study", default="", choices=["", "transfer", "prefill", "xcd"],
                     help="transfer: block-wise versus element-wise host-to-device gather over miss fractions (prints one JSON line per point); "
-                         "prefill: sparse prefill of one chunk at the end of the 8B-shaped context (one JSON line)")
+                         "prefill: sparse prefill of one chunk at the end of the 8B-shaped context (one JSON line); "
+                         "xcd: per-XCD timing of the attention kernel's workgroups over several layer states (one JSON line)")
     ap.add_argument("--prefill-batch", type=int, default=4)
     ap.add_argument("--prefill-chunk", type=int, default=2048, help="query positions per chunk (multiple of 64)")
     ap.add_argument("--prefill-all", action="store_true",
@@ -329,6 +331,86 @@ def longgen_bench(args):
     print(json.dumps(line), flush=True)
 
 
+def xcd_study(args):
+    """Where the attention kernel's time goes across the chip: per-workgroup start / end stamps (nosa_set_trace) of
+    the stand-alone attention launch on the 8B-shaped workload, grouped by the XCD a workgroup ran on, for several
+    layer states (distinct pool allocations) visited several times each.  One JSON line."""
+    import numpy as np
+    import torch
+    import paper_2510_13602_amd as nosa
+    from nosa_inputs import CONFIGS, QueryStream, make_layer
+    from paper_2510_13602_amd.runtime import LayerCache, pinned_like
+    dev = "cuda:0"
+    w = CONFIGS[args.workload if args.workload in ("3b", "8b") else "8b"]
+    L = args.layers or 6
+    params = nosa.make_params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                              k_blocks=w.k_blocks, kq_blocks=w.kq_blocks, sink_blocks=w.sink_blocks,
+                              window_blocks=w.window_blocks, gpu_slots=w.gpu_slots, max_blocks=w.max_blocks,
+                              n_sub_max=w.n_sub_max, dtype=w.dtype)
+    ctx = nosa.Nosa(params, device=dev)
+    ctx.set_overlap(False)
+    if args.splits:
+        ctx.set_splits(args.splits)
+    lay = make_layer(w, args.seed, 0, device=dev)
+    host = (pinned_like(lay["host_k"]), pinned_like(lay["host_v"]), pinned_like(lay["host_bias"]))
+    del lay
+    n_tok = torch.full((w.batch,), w.context, dtype=torch.int32)
+    layers = []
+    for l in range(L):
+        lc = LayerCache(ctx, *host, n_tok)
+        if l % 2 == 1 and args.xcd_shift_kib:
+            # odd layer states: the same pools, placed args.xcd_shift_kib further into their allocations, so that every
+            # unit's blocks sit at different physical-address bits while the workgroup-to-XCD assignment stays the same
+            for name in ("pool_k", "pool_v"):
+                t = getattr(lc, name)
+                shift = args.xcd_shift_kib * 1024 // t.element_size()
+                big = torch.zeros(t.numel() + shift, dtype=t.dtype, device=dev)
+                setattr(lc, name, big[shift:].view(t.shape))
+        if l == 0:
+            lc.rebuild_pooled()
+        else:
+            lc.k_pooled.copy_(layers[0].k_pooled)
+            lc.se_pooled.copy_(layers[0].se_pooled)
+        layers.append(lc)
+    q = QueryStream(w, args.seed, 0, device=dev).next(0)
+    for lc in layers:                      # cold start: every layer state ends up with the same selection in its own pool
+        lc.step(q)
+    torch.cuda.synchronize()
+    n_wg = ctx.splits * w.units
+    trace = torch.zeros((n_wg, 4), dtype=torch.int64, device=dev)
+    ctx.set_trace(trace)
+    visits = 4
+    per_layer = []
+    for l, lc in enumerate(layers):
+        durs, ends, xcds = [], [], None
+        for v in range(visits + 1):
+            for other in layers:           # touch every other pool in between, so that no visit finds its pool in a cache
+                if other is not lc:
+                    other.decode(q)
+            lc.decode(q)
+            torch.cuda.synchronize()
+            t = trace.cpu().numpy()
+            if v == 0:
+                continue                   # warm-up visit
+            t0 = t[:, 0].min()
+            durs.append((t[:, 1] - t[:, 0]) / 100.0)      # us
+            ends.append((t[:, 1] - t0) / 100.0)
+            xcds = t[:, 2]
+        dur, end = np.mean(durs, axis=0), np.mean(ends, axis=0)
+        by = []
+        for x in range(8):
+            m = xcds == x
+            by.append({"xcd": x, "workgroups": int(m.sum()), "dur_mean_us": float(dur[m].mean()) if m.any() else None,
+                       "dur_min_us": float(dur[m].min()) if m.any() else None, "dur_max_us": float(dur[m].max()) if m.any() else None,
+                       "last_end_us": float(end[m].max()) if m.any() else None})
+        per_layer.append({"layer_state": l, "pool_shift_kib": args.xcd_shift_kib if l % 2 == 1 else 0, "kernel_span_us": float(end.max()), "workgroup_dur_mean_us": float(dur.mean()),
+                          "round_robin_matches_xcc_id": bool(((np.arange(n_wg) % 8) == xcds).all()), "by_xcd": by})
+    ctx.set_trace(None)
+    ctx.close()
+    print(json.dumps({"study": "xcd", "workload": w.name, "workgroups": n_wg, "splits": n_wg // w.units, "visits_averaged": visits,
+                      "layers": per_layer}), flush=True)
+
+
 def prefill_study(args):
     """Sparse prefill of the last chunk of an 8B-shaped context: every query position selects its blocks
     (score + selection kernels on a virtual batch of positions) and attends to them on the matrix cores.
@@ -465,6 +547,8 @@ def main():
         return transfer_study(args)
     if args.study == "prefill":
         return prefill_study(args)
+    if args.study == "xcd":
+        return xcd_study(args)
     if args.workload == "longgen":
         return longgen_bench(args)
     w = CONFIGS[args.workload]

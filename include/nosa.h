@@ -329,6 +329,12 @@ int nosa_prefill_attend(nosa_ctx* ctx, const void* q_chunk, const void* cache_k,
  * launches since the last read, and resets the counters.  At most 4096 launches per kernel are
  * kept between reads.                                                                           */
 int nosa_timing_enable(nosa_ctx* ctx, int on);
+
+/* Diagnostics: with a trace buffer set (dev, 4 x uint64 per workgroup, capacity in workgroups), every
+ * workgroup of the stand-alone attention kernel (nosa_sparse_decode with no fetch in flight) records
+ * {start, end} in ticks of the GPU's 100 MHz real-time counter, the XCD it ran on and its index.  A
+ * launch with more workgroups (units x splits) than the capacity records nothing.  NULL switches it off. */
+int nosa_set_trace(nosa_ctx* ctx, uint64_t* dev_buf, int32_t capacity_workgroups);
 int nosa_timing_read(nosa_ctx* ctx, int kernel, double* total_ms, int32_t* launches);
 
 #ifdef __cplusplus

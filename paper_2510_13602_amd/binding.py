@@ -28,7 +28,7 @@ EXPORTS = [
     "nosa_set_splits", "nosa_get_splits", "nosa_set_merge_in_kernel", "nosa_set_overlap", "nosa_set_fetch_workgroups", "nosa_last_error", "nosa_block_score",
     "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_sparse_decode_static", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_fetch_tokens", "nosa_decode_step", "nosa_set_fused_select", "nosa_graph_create", "nosa_graph_begin", "nosa_graph_end", "nosa_graph_launch",
     "nosa_graph_destroy", "nosa_prefill_select", "nosa_prefill_attend", "nosa_timing_enable",
-    "nosa_timing_read",
+    "nosa_timing_read", "nosa_set_trace",
 ]
 
 
@@ -97,6 +97,7 @@ def load_library() -> ctypes.CDLL:
     lib.nosa_graph_launch.argtypes = [vp, vp]
     lib.nosa_graph_destroy.argtypes = [vp]
     lib.nosa_timing_enable.argtypes = [vp, ctypes.c_int]
+    lib.nosa_set_trace.argtypes = [vp, vp, ctypes.c_int32]
     lib.nosa_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     for name in EXPORTS:
         if name not in ("nosa_workspace_bytes", "nosa_last_error"):
@@ -199,6 +200,15 @@ class Nosa:
 
     def set_fetch_workgroups(self, n: int) -> None:
         self._check(self.lib.nosa_set_fetch_workgroups(self._ctx, n))
+
+    def set_trace(self, buf: Optional[torch.Tensor]) -> None:
+        """``buf``: int64 device tensor [workgroups, 4] (or None to switch the trace off)."""
+        if buf is None:
+            self._check(self.lib.nosa_set_trace(self._ctx, None, 0))
+        else:
+            if not (buf.is_cuda and buf.dtype == torch.int64 and buf.is_contiguous() and buf.dim() == 2 and buf.shape[1] == 4):
+                raise ValueError("trace buffer must be a contiguous int64 device tensor [workgroups, 4]")
+            self._check(self.lib.nosa_set_trace(self._ctx, ctypes.c_void_p(buf.data_ptr()), buf.shape[0]))
 
     def timing_enable(self, on: bool) -> None:
         self._check(self.lib.nosa_timing_enable(self._ctx, 1 if on else 0))

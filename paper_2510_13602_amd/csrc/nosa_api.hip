@@ -570,6 +570,15 @@ int nosa_append(nosa_ctx* ctx, const void* k_new, const void* v_new, const float
                              se_pooled, se_blk, n_tokens, slot_of_block, block_of_slot);
 }
 
+int nosa_set_trace(nosa_ctx* ctx, uint64_t* dev_buf, int32_t capacity_workgroups) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, capacity_workgroups >= 0 && (dev_buf || capacity_workgroups == 0), NOSA_EINVAL,
+               "nosa_set_trace: a buffer is needed for a capacity of %d workgroups", capacity_workgroups);
+  ctx->trace = (unsigned long long*)dev_buf;
+  ctx->trace_capacity = dev_buf ? capacity_workgroups : 0;
+  return NOSA_OK;
+}
+
 int nosa_timing_enable(nosa_ctx* ctx, int on) {
   NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
   ctx->timing = on != 0;

@@ -60,6 +60,7 @@ struct DecodeArgs {
   float* part_o;   // [units][splits][G][D] un-normalised
   float* part_ml;  // [units][splits][G][2]  (m in log2 domain, l)
   int32_t* arrived;   // [units] workgroups of a unit that have written their partial result (zero between launches)
+  unsigned long long* trace;   // diagnostics (nosa_set_trace), else NULL: 4 words per workgroup
   void* out;
   float* lse;
   const int32_t* load_list;   // phases 1 and 2: the (block, slot) pairs of the fetch in flight
@@ -260,6 +261,9 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
   const int wave = tid / kWave;
   const int r = lane / kLPR;   // row-group within the wave
   const int c = lane % kLPR;   // 16-byte slice of a 128-byte line
+
+  unsigned long long t_start = 0;
+  if (!OVERLAP && a.trace && tid == 0) t_start = __builtin_amdgcn_s_memrealtime();   // 100 MHz real-time counter
 
   const int T = a.n_tokens[b];
   int n_sel;   // entries of the work table
@@ -550,6 +554,13 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
         if (tid == 0) __hip_atomic_store(a.arrived + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
+    if (a.trace && tid == 0) {   // when and where this workgroup ran: start, end, XCD (hardware register XCC_ID), its index
+      unsigned long long* t = a.trace + (size_t)blockIdx.x * 4;
+      t[0] = t_start;
+      t[1] = __builtin_amdgcn_s_memrealtime();
+      t[2] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 0xfu;
+      t[3] = blockIdx.x;
+    }
   }
 }
 
@@ -681,6 +692,7 @@ int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* 
   a.arrived = ctx->merge_in_kernel ? (int32_t*)ws : nullptr;
   a.part_o = ws ? (float*)((char*)ws + counter_bytes) : nullptr;
   a.part_ml = a.part_o ? a.part_o + (size_t)ctx->units * S * G * D : nullptr;
+  a.trace = (ctx->trace && ctx->trace_capacity >= S * ctx->units) ? ctx->trace : nullptr;
   a.out = out; a.lse = lse;
   a.load_list = load_list; a.n_load = n_load;
   a.n_kv_heads = p.n_kv_heads; a.gpu_slots = p.gpu_slots; a.k_blocks = p.k_blocks; a.max_blocks = p.max_blocks;

@@ -48,6 +48,8 @@ struct nosa_ctx {
   void* ws = nullptr;
   size_t ws_bytes = 0;
   void* static_scratch = nullptr;   // this device's copy of the library's static scratch array
+  unsigned long long* trace = nullptr;   // nosa_set_trace: per-workgroup time stamps of the attention kernel (dev)
+  int trace_capacity = 0;                // workgroups the trace buffer holds
   bool timing = false;
   bool capturing = false;             // between nosa_graph_begin and nosa_graph_end
   bool timing_before_capture = false;

@@ -143,6 +143,43 @@ def test_split_merge_inside_the_kernel_equals_the_combine_launch(dtype, d, Hq, H
     ctx.close()
 
 
+def test_attention_trace_records_one_row_per_workgroup():
+    """nosa_set_trace: start <= end on the real-time counter, an XCD number in 0..7, the workgroup's own index; a
+    buffer that is too small for the launch is left alone; the output does not depend on the trace."""
+    T = 64 * 20 + 9
+    w = small_workload(batch=3, n_q_heads=8, n_kv_heads=2, head_dim=128, context=T, k_blocks=12, kq_blocks=1, gpu_slots=15,
+                       dtype="bf16")
+    rng = np.random.default_rng(3)
+    layer = make_layer(w, seed=23, layer=0)
+    sel, n_sel = _random_selection(w, rng, T)
+    pk, pv, pb, sob = _scattered_pool(w, layer, sel, n_sel, seed=1)
+    td = w.torch_dtype
+    args = (from_np(pk, td), from_np(pv, td), from_np(pb, torch.float32), torch.from_numpy(sel).to(DEV),
+            torch.from_numpy(n_sel).to(DEV), torch.from_numpy(sob).to(DEV), torch.full((w.batch,), T, dtype=torch.int32, device=DEV))
+    ctx = nosa.Nosa(gpu_params(w), device=DEV)
+    ctx.set_splits(3)
+    q = QueryStream(w, 23, 0).next(0).to(DEV)
+    n_wg = 3 * w.units
+    outs = []
+    for cap in (None, n_wg, n_wg - 1):
+        trace = torch.full((max(cap or 1, 1), 4), -1, dtype=torch.int64, device=DEV)
+        ctx.set_trace(None if cap is None else trace)
+        out = torch.empty((w.batch, 8, 128), dtype=td, device=DEV)
+        ctx.nosa_sparse_decode(q, *args, out)
+        torch.cuda.synchronize()
+        outs.append(to_np(out).copy())
+        t = trace.cpu().numpy()
+        if cap == n_wg:
+            assert (t[:, 1] >= t[:, 0]).all() and (t[:, 0] > 0).all()
+            assert ((t[:, 2] >= 0) & (t[:, 2] < 8)).all()
+            assert (t[:, 3] == np.arange(n_wg)).all()
+        else:
+            assert (t == -1).all()
+    ctx.set_trace(None)
+    assert outs[0].tobytes() == outs[1].tobytes() == outs[2].tobytes()
+    ctx.close()
+
+
 def test_sparse_decode_empty_and_single_token():
     """n_sel = 0 gives a zero output row and lse = -inf; T = 1 attends the one token."""
     w = small_workload(batch=2, n_q_heads=4, n_kv_heads=2, head_dim=64, context=1, k_blocks=4, kq_blocks=1,
