@@ -43,6 +43,7 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--kq", type=int, default=0, help="override the query-aware budget Kq (blocks); Ke shrinks accordingly")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--heads", default="", help="override the head counts: 'Hq,Hkv' (e.g. 32,2 for the paper's own 8B model)")
     ap.add_argument("--slots", type=int, default=0,
                     help="GPU pool slots C per unit (default: the workload's, C = K for the 8B shape); C > K keeps blocks beyond the selection resident")
     ap.add_argument("--victim-policy", type=int, default=-1, choices=[-1, 0, 1],
@@ -51,6 +52,8 @@ def parse_args():
     ap.add_argument("--gen-tokens", type=int, default=16384, help="long-generation workload: tokens generated per layer state")
     ap.add_argument("--no-fused-select", action="store_true",
                     help="run block score and selection as two kernels inside nosa_decode_step (default: one kernel, scores stay on chip)")
+    ap.add_argument("--attention-kernel", type=int, default=0, choices=[0, 1, 2],
+                    help="0 chosen from the shape, 1 vector-ALU attention kernel, 2 matrix-core attention kernel (bf16)")
     ap.add_argument("--no-larger-pool", action="store_true",
                     help="skip the second measurement of the headline workload with C = 96 slots and importance-ranked victims")
     ap.add_argument("--locality-steps", type=int, default=64, help="untimed steps after the timed regions that record the miss count of every step")
@@ -226,6 +229,7 @@ def longgen_bench(args):
                               n_sub_max=w.n_sub_max, dtype=w.dtype, victim_policy=w.victim_policy)
     ctx = nosa.Nosa(params, stream=stream, device=dev)
     ctx.set_fused_select(not args.no_fused_select)
+    ctx.set_attention_kernel(args.attention_kernel)
     layers, streams = [], []
     for l in range(L):
         lay = make_layer(w, args.seed, l, device=dev)
@@ -560,9 +564,12 @@ def main():
         w = w.replace(victim_policy=args.victim_policy)
     if args.batch:
         w = w.replace(batch=args.batch)
+    if args.heads:
+        hq, hkv = (int(x) for x in args.heads.split(","))
+        w = w.replace(n_q_heads=hq, n_kv_heads=hkv)
     line = measure(args, w)
     headline = (args.workload == "8b" and not args.kq and not args.slots and args.victim_policy < 0 and not args.resident
-                and not args.batch)
+                and not args.batch and not args.heads)
     if headline and not args.no_larger_pool:
         # The same workload with half as many slots again per unit and importance-ranked victims: the paper's
         # pool holds exactly the selection (C = K, the headline above); a larger pool keeps recently used
@@ -599,6 +606,7 @@ def measure(args, w):
         ctx.set_fetch_workgroups(args.fetch_wgs)
     ctx.set_overlap(False)      # the timed region runs every kernel alone on one stream; see below
     ctx.set_fused_select(not args.no_fused_select)
+    ctx.set_attention_kernel(args.attention_kernel)
 
     # host pools: every block of the cache, pinned; drawn on the GPU (seeded) and copied out
     hosts = []

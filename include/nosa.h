@@ -102,6 +102,17 @@ int nosa_set_workspace(nosa_ctx* ctx, void* dev_ws, size_t bytes);
 int nosa_set_splits(nosa_ctx* ctx, int splits);
 int nosa_get_splits(const nosa_ctx* ctx);
 
+/* Which kernel nosa_sparse_decode runs.
+ * 2, the matrix-core kernel (bf16 only): the (up to 16) heads of a group are the N dimension of
+ * v_mfma_f32_16x16x32_bf16, K feeds the score product straight from global memory, V is transposed
+ * through LDS, the softmax weights are rounded to bf16 (nearest even) for the second product while the row
+ * sums keep the unrounded ones.  Its cost does not depend on G: it streams K and V at the same rate for
+ * G = 1 and for the G = 16 of the paper's own 3B and 8B models (32 query / 2 KV heads).
+ * 1, the vector-ALU kernel (fp32 and bf16): K and V stream through registers in full lines, q.k by packed dot
+ * products, P.V by fp32 FMAs; 4 G flops per byte, so it falls behind from G = 6 on and spills at G = 16.
+ * 0 (default): 2 for bf16, 1 for fp32.  A request for 2 on an fp32 context runs 1.                      */
+int nosa_set_attention_kernel(nosa_ctx* ctx, int which);
+
 /* With several splits, who merges the partial results of a unit: 1 (default) the workgroup of the
  * attention kernel that finds all the others of its unit done (an arrival counter per unit, nobody
  * waits); 0 a separate combine launch.  Same arithmetic in the same order, same result.           */

@@ -25,7 +25,7 @@ STATIC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = [
     "nosa_validate_params", "nosa_create", "nosa_destroy", "nosa_workspace_bytes", "nosa_set_workspace",
-    "nosa_set_splits", "nosa_get_splits", "nosa_set_merge_in_kernel", "nosa_set_overlap", "nosa_set_fetch_workgroups", "nosa_last_error", "nosa_block_score",
+    "nosa_set_splits", "nosa_get_splits", "nosa_set_merge_in_kernel", "nosa_set_attention_kernel", "nosa_set_overlap", "nosa_set_fetch_workgroups", "nosa_last_error", "nosa_block_score",
     "nosa_select", "nosa_fetch", "nosa_sparse_decode", "nosa_sparse_decode_static", "nosa_pool_blocks", "nosa_append", "nosa_split_qkv_evict", "nosa_fetch_tokens", "nosa_decode_step", "nosa_set_fused_select", "nosa_graph_create", "nosa_graph_begin", "nosa_graph_end", "nosa_graph_launch",
     "nosa_graph_destroy", "nosa_prefill_select", "nosa_prefill_attend", "nosa_timing_enable",
     "nosa_timing_read", "nosa_set_trace",
@@ -76,6 +76,7 @@ def load_library() -> ctypes.CDLL:
     lib.nosa_set_splits.argtypes = [vp, ctypes.c_int]
     lib.nosa_get_splits.argtypes = [vp]
     lib.nosa_set_merge_in_kernel.argtypes = [vp, ctypes.c_int]
+    lib.nosa_set_attention_kernel.argtypes = [vp, ctypes.c_int]
     lib.nosa_set_overlap.argtypes = [vp, ctypes.c_int]
     lib.nosa_set_fetch_workgroups.argtypes = [vp, ctypes.c_int]
     lib.nosa_set_fused_select.argtypes = [vp, ctypes.c_int]
@@ -188,6 +189,10 @@ class Nosa:
 
     def set_splits(self, s: int) -> None:
         self._check(self.lib.nosa_set_splits(self._ctx, s))
+
+    def set_attention_kernel(self, which: int) -> None:
+        """0 chosen from the shape, 1 vector-ALU kernel, 2 matrix-core kernel."""
+        self._check(self.lib.nosa_set_attention_kernel(self._ctx, int(which)))
 
     def set_merge_in_kernel(self, on: bool) -> None:
         self._check(self.lib.nosa_set_merge_in_kernel(self._ctx, 1 if on else 0))

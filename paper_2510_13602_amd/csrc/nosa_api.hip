@@ -184,6 +184,13 @@ int nosa_set_workspace(nosa_ctx* ctx, void* dev_ws, size_t bytes) {
   return nosa::decode_zero_counters(ctx, dev_ws);
 }
 
+int nosa_set_attention_kernel(nosa_ctx* ctx, int which) {
+  NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
+  NOSA_REQUIRE(ctx, which >= 0 && which <= 2, NOSA_EINVAL, "nosa_set_attention_kernel: %d not in {0, 1, 2}", which);
+  ctx->attention_kernel = which;
+  return NOSA_OK;
+}
+
 int nosa_set_merge_in_kernel(nosa_ctx* ctx, int on) {
   NOSA_REQUIRE(ctx, ctx, NOSA_EINVAL, "ctx is NULL");
   ctx->merge_in_kernel = on ? 1 : 0;

@@ -228,45 +228,13 @@ __device__ __forceinline__ void merge_arrived(const float* part_o, const float* 
   }
 }
 
-// OVERLAP = false: the plain kernel (phase 0).  OVERLAP = true: the two launches that bracket a
-// gather in flight (phase 1: resident blocks only; phase 2: fetched blocks, then the merge); a
-// separate instantiation so that profiles list the stand-alone kernel on its own.
-template <int DT, int D, int G, bool OVERLAP>
-__global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeArgs a) {
-  const int phase = OVERLAP ? a.phase : 0;
-  const bool has_bias = a.pool_bias != nullptr;
-  using V = Vec<DT>;
-  constexpr int EPL = V::kElems;                 // elements per 16-byte load
-  constexpr int RP = D / EPL;                    // row pitch in 16-byte vectors
-  constexpr int VPL = RP / kLPR;                 // loads per lane and row (row_bytes / 128)
-  constexpr int STEPS = kLoads / VPL;            // steps (of 8 rows) per tile
-  constexpr int TILE = kRPW * STEPS;             // tokens per tile
-  constexpr int TPB = kBlockTokens / TILE;       // tiles per block
-  constexpr int LE = VPL * EPL;                  // elements of a row held by one lane
-  static_assert(VPL >= 1 && STEPS >= 1 && TPB >= 1 && TPB * TILE == kBlockTokens, "tile must divide the block");
-  constexpr float NEG_INF = -INFINITY;
-
-  __shared__ int s_slot[kMaxSelBlocks];
-  __shared__ int s_valid[kMaxSelBlocks];
-  __shared__ float s_m[kWaves][G];
-  __shared__ float s_l[kWaves][G];
-  __shared__ float s_acc[kWaves][G][D];
-
-  const int unit = blockIdx.x / a.splits;
-  const int split = blockIdx.x % a.splits;
-  const int b = unit / a.n_kv_heads;
-  const int h = unit % a.n_kv_heads;
-  const int tid = threadIdx.x;
-  const int lane = tid % kWave;
-  const int wave = tid / kWave;
-  const int r = lane / kLPR;   // row-group within the wave
-  const int c = lane % kLPR;   // 16-byte slice of a 128-byte line
-
-  unsigned long long t_start = 0;
-  if (!OVERLAP && a.trace && tid == 0) t_start = __builtin_amdgcn_s_memrealtime();   // 100 MHz real-time counter
-
-  const int T = a.n_tokens[b];
-  int n_sel;   // entries of the work table
+// Resolves the blocks a workgroup attends into (slot, valid tokens) pairs in LDS, once per workgroup.
+// phase 0: the whole selection; phase 1: the selection minus the blocks of the fetch in flight; phase 2: only
+// those blocks.  Returns the number of table entries.  Followed by a barrier in the caller.
+template <bool OVERLAP>
+__device__ __forceinline__ int decode_work_table(const DecodeArgs& a, const int phase, const int unit, const int tid,
+                                                 const int T, int* s_slot, int* s_valid) {
+  int n_sel;
   if (phase == 2) {
     // the blocks that were fetched for this step: (block, slot) pairs of the load list
     n_sel = min(a.n_load[unit], a.k_blocks);
@@ -311,6 +279,145 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
       s_valid[i] = valid;
     }
   }
+  return n_sel;
+}
+
+// Last part of an attention workgroup: the per-wave states (m in the log2 domain, l, un-normalised O) that the
+// waves left in LDS are merged; the result is the output (one split, or phase 2, which also folds in the
+// phase-1 partial results), or a partial result, which the last workgroup of the unit to arrive merges.
+template <int DT, int D, int G, bool OVERLAP>
+__device__ __forceinline__ void decode_finish(const DecodeArgs& a, const int phase, const int unit, const int split,
+                                              const int b, const int h, const int tid, const float (*s_m)[G],
+                                              const float (*s_l)[G], const float (*s_acc)[G][D],
+                                              const unsigned long long t_start) {
+  constexpr float NEG_INF = -INFINITY;
+  // ---- merge the waves; write the partial result (or the output when there is one split) ----
+  for (int idx = tid; idx < G * D; idx += kThreads) {
+    const int g = idx / D, e = idx % D;
+    float M = s_m[0][g];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w][g]);
+    float L = 0.f, O = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float sc = (s_m[w][g] == NEG_INF) ? 0.f : fast_exp2(s_m[w][g] - M);
+      L = fmaf(s_l[w][g], sc, L);
+      O = fmaf(s_acc[w][g][e], sc, O);
+    }
+    if (phase == 2) {
+      // fold in the partial results of the resident blocks (written by the phase-1 launch)
+      const size_t p0 = ((size_t)unit * a.merge_splits) * G + g;
+      float M2 = M;
+      for (int sp = 0; sp < a.merge_splits; ++sp) M2 = fmaxf(M2, a.part_ml[(p0 + (size_t)sp * G) * 2]);
+      const float sc0 = (M == NEG_INF) ? 0.f : fast_exp2(M - M2);
+      L *= sc0;
+      O *= sc0;
+      for (int sp = 0; sp < a.merge_splits; ++sp) {
+        const size_t pi = p0 + (size_t)sp * G;
+        const float ms = a.part_ml[pi * 2];
+        const float sc = (ms == NEG_INF) ? 0.f : fast_exp2(ms - M2);
+        L = fmaf(a.part_ml[pi * 2 + 1], sc, L);
+        O = fmaf(a.part_o[pi * D + e], sc, O);
+      }
+      M = M2;
+    }
+    if (phase == 2 || (a.splits == 1 && phase == 0)) {
+      const size_t o = ((size_t)b * a.n_kv_heads * G + (size_t)h * G + g) * D + e;
+      store_out(a.out, o, L > 0.f ? O / L : 0.f, DT);
+      if (a.lse && e == 0) a.lse[(size_t)b * a.n_kv_heads * G + h * G + g] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : NEG_INF;
+    } else {
+      const size_t pidx = ((size_t)unit * a.splits + split) * G + g;
+      if (!OVERLAP && a.arrived) {       // read by another workgroup of this very launch
+        part_store<true>(a.part_o + pidx * D + e, O);
+        if (e == 0) {
+          part_store<true>(a.part_ml + pidx * 2, M);
+          part_store<true>(a.part_ml + pidx * 2 + 1, L);
+        }
+      } else {
+        a.part_o[pidx * D + e] = O;
+        if (e == 0) {
+          a.part_ml[pidx * 2] = M;
+          a.part_ml[pidx * 2 + 1] = L;
+        }
+      }
+    }
+  }
+  if constexpr (!OVERLAP) {
+    // Several splits and a counter array: the workgroup that finds all the others of its unit done merges
+    // their partial results into the output, which saves the separate combine launch.  Every lane waits
+    // until its partial-result stores are acknowledged, the workgroup meets, one lane bumps the unit's
+    // counter; whoever reads splits - 1 there is the last arrival and does the merge.  Nobody waits for
+    // anybody else.  The last arrival puts the counter back to zero for the next launch.
+    if (a.splits > 1 && a.arrived != nullptr) {
+      __shared__ int s_last;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      wait_vector_memory();
+      __syncthreads();
+      if (tid == 0) {
+        const int before = __hip_atomic_fetch_add(a.arrived + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = before == a.splits - 1;
+      }
+      __syncthreads();
+      if (s_last) {
+        wait_vector_memory();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        // all partial values in flight at once while that fits the registers: (outputs per lane) x (splits) x 3
+        constexpr int kPerLane = (G * D + kThreads - 1) / kThreads;
+        if (a.splits <= 4 && kPerLane <= 8) merge_arrived<DT, D, G, 4>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, a.splits);
+        else if (a.splits <= 8 && kPerLane <= 4) merge_arrived<DT, D, G, 8>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, a.splits);
+        else combine_unit<DT, true>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, G, D, a.splits);
+        if (tid == 0) __hip_atomic_store(a.arrived + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    if (a.trace && tid == 0) {   // when and where this workgroup ran: start, end, XCD (hardware register XCC_ID), its index
+      unsigned long long* t = a.trace + (size_t)blockIdx.x * 4;
+      t[0] = t_start;
+      t[1] = __builtin_amdgcn_s_memrealtime();
+      t[2] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 0xfu;
+      t[3] = blockIdx.x;
+    }
+  }
+}
+
+// OVERLAP = false: the plain kernel (phase 0).  OVERLAP = true: the two launches that bracket a
+// gather in flight (phase 1: resident blocks only; phase 2: fetched blocks, then the merge); a
+// separate instantiation so that profiles list the stand-alone kernel on its own.
+template <int DT, int D, int G, bool OVERLAP>
+__global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeArgs a) {
+  const int phase = OVERLAP ? a.phase : 0;
+  const bool has_bias = a.pool_bias != nullptr;
+  using V = Vec<DT>;
+  constexpr int EPL = V::kElems;                 // elements per 16-byte load
+  constexpr int RP = D / EPL;                    // row pitch in 16-byte vectors
+  constexpr int VPL = RP / kLPR;                 // loads per lane and row (row_bytes / 128)
+  constexpr int STEPS = kLoads / VPL;            // steps (of 8 rows) per tile
+  constexpr int TILE = kRPW * STEPS;             // tokens per tile
+  constexpr int TPB = kBlockTokens / TILE;       // tiles per block
+  constexpr int LE = VPL * EPL;                  // elements of a row held by one lane
+  static_assert(VPL >= 1 && STEPS >= 1 && TPB >= 1 && TPB * TILE == kBlockTokens, "tile must divide the block");
+  constexpr float NEG_INF = -INFINITY;
+
+  __shared__ int s_slot[kMaxSelBlocks];
+  __shared__ int s_valid[kMaxSelBlocks];
+  __shared__ float s_m[kWaves][G];
+  __shared__ float s_l[kWaves][G];
+  __shared__ float s_acc[kWaves][G][D];
+
+  const int unit = blockIdx.x / a.splits;
+  const int split = blockIdx.x % a.splits;
+  const int b = unit / a.n_kv_heads;
+  const int h = unit % a.n_kv_heads;
+  const int tid = threadIdx.x;
+  const int lane = tid % kWave;
+  const int wave = tid / kWave;
+  const int r = lane / kLPR;   // row-group within the wave
+  const int c = lane % kLPR;   // 16-byte slice of a 128-byte line
+
+  unsigned long long t_start = 0;
+  if (!OVERLAP && a.trace && tid == 0) t_start = __builtin_amdgcn_s_memrealtime();   // 100 MHz real-time counter
+
+  const int T = a.n_tokens[b];
+  const int n_sel = decode_work_table<OVERLAP>(a, phase, unit, tid, T, s_slot, s_valid);   // entries of the work table
 
   // q slices of this lane for all heads of the group: line v of the row, 16-byte slice c
   V qv[G][VPL];
@@ -478,90 +585,231 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
   }
   __syncthreads();
 
-  // ---- merge the waves; write the partial result (or the output when there is one split) ----
-  for (int idx = tid; idx < G * D; idx += kThreads) {
-    const int g = idx / D, e = idx % D;
-    float M = s_m[0][g];
+  decode_finish<DT, D, G, OVERLAP>(a, phase, unit, split, b, h, tid, s_m, s_l, s_acc, t_start);
+}
+
+// ---- the same attention on the matrix cores, for large query groups ------------------------------------
+// With G query heads per KV head the vector kernel above does 4 G flops per byte: at G = 8 it is bound by
+// its arithmetic and registers, at G = 16 (the paper's own 3B and 8B models: 32 query / 2 KV heads) it
+// spills.  A group of up to 16 heads is exactly one N dimension of v_mfma_f32_16x16x32_bf16, so this
+// kernel (bf16 only) computes, per tile of 32 tokens and per wave,
+//   S^T = K Q^T    A = 16 token rows of K straight from global memory in operand order (lane = token row
+//                  l % 16, 16-byte slice l / 16 of a 64-byte piece of the row), B = Q^T in registers for the
+//                  whole kernel (lane = head l % 16, zero for l % 16 >= G).  In the C layout a lane owns one
+//                  head (column l % 16) and 4 tokens per 16-token tile.
+//   O^T += V^T P^T A = V^T from this wave's private LDS tile, B = P^T = the lane's own 8 weights (bf16).
+//                  In the C layout a lane owns one head again, so the running maximum, the sum and the
+//                  rescale of O all stay in the lane; only the tile maximum is exchanged between the four
+//                  lanes of a head (two shuffles per tile).
+// V arrives in full 128-byte lines as [token][d] and is transposed on its way into LDS: two tokens of one
+// column share a 32-bit word (byte permute), the words go to row d of a [d][32 positions] tile whose 16-byte
+// chunks are XOR-swizzled.  The position of a token inside a row is chosen so that the 8 weights a lane
+// holds after the score product are 8 consecutive positions (a sum over tokens does not care about their
+// order).  LDS is private to a wave: its loads and stores execute in order, no barrier inside the loop.
+// Weights are rounded to bf16 (nearest even) for the second product; the row sums use the unrounded ones.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {   // round to nearest even
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// x of lanes l, l ^ 16, l ^ 32, l ^ 48 combined: the four lanes that hold one head
+__device__ __forceinline__ float head_max(float x) {
+  x = fmaxf(x, __shfl_xor(x, 16));
+  return fmaxf(x, __shfl_xor(x, 32));
+}
+
+template <int D, int G, bool OVERLAP>
+__global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeArgs a) {
+  constexpr int DT = NOSA_DTYPE_BF16;
+  constexpr int KC = D / 32;             // k-steps of the score product
+  constexpr int NDT = D / 16;            // 16-row tiles of O^T
+  constexpr int ROWB = D * 2;            // bytes per K or V row
+  constexpr int VPL = ROWB / 128;        // 128-byte lines per row
+  constexpr int TILE = 32;               // tokens per tile
+  constexpr int TPB = kBlockTokens / TILE;
+  constexpr int kVt = D * 64;            // bytes of one wave's V^T tile: D rows x 32 positions x 2 B
+  constexpr float NEG_INF = -INFINITY;
+  constexpr float kLog2e = 1.4426950408889634f;
+  static_assert(G <= 16, "the heads of a group are the 16 columns of one matrix-core tile");
+  const int phase = OVERLAP ? a.phase : 0;
+
+  __shared__ int s_slot[kMaxSelBlocks];
+  __shared__ int s_valid[kMaxSelBlocks];
+  __shared__ float s_m[kWaves][G];
+  __shared__ float s_l[kWaves][G];
+  __shared__ __align__(16) unsigned char s_buf[kWaves * kVt];   // V^T tiles in the loop, the waves' O afterwards
+  static_assert(sizeof(float) * kWaves * G * D <= sizeof(s_buf), "the per-wave results must fit the tile buffer");
+  float (*s_acc)[G][D] = reinterpret_cast<float (*)[G][D]>(s_buf);
+
+  const int unit = blockIdx.x / a.splits;
+  const int split = blockIdx.x % a.splits;
+  const int b = unit / a.n_kv_heads;
+  const int h = unit % a.n_kv_heads;
+  const int tid = threadIdx.x;
+  const int lane = tid % kWave;
+  const int wave = tid / kWave;
+  const int l16 = lane % 16, g4 = lane / 16;   // operand / accumulator coordinates
+  const int r8 = lane / 8, c8 = lane % 8;      // coordinates of the V loads: row pair, 16-byte slice of a line
+
+  unsigned long long t_start = 0;
+  if (!OVERLAP && a.trace && tid == 0) t_start = __builtin_amdgcn_s_memrealtime();
+
+  const int T = a.n_tokens[b];
+  const int n_sel = decode_work_table<OVERLAP>(a, phase, unit, tid, T, s_slot, s_valid);
+
+  // Q^T: head l16 (zero beyond the group), d = 32 kc + 8 g4 .. + 7
+  bf16x8_t qb[KC];
+  {
+    const char* qp = (const char*)a.q + ((size_t)b * a.n_kv_heads * G + (size_t)h * G + (l16 < G ? l16 : 0)) * ROWB;
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w][g]);
-    float L = 0.f, O = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const float sc = (s_m[w][g] == NEG_INF) ? 0.f : fast_exp2(s_m[w][g] - M);
-      L = fmaf(s_l[w][g], sc, L);
-      O = fmaf(s_acc[w][g][e], sc, O);
-    }
-    if (phase == 2) {
-      // fold in the partial results of the resident blocks (written by the phase-1 launch)
-      const size_t p0 = ((size_t)unit * a.merge_splits) * G + g;
-      float M2 = M;
-      for (int sp = 0; sp < a.merge_splits; ++sp) M2 = fmaxf(M2, a.part_ml[(p0 + (size_t)sp * G) * 2]);
-      const float sc0 = (M == NEG_INF) ? 0.f : fast_exp2(M - M2);
-      L *= sc0;
-      O *= sc0;
-      for (int sp = 0; sp < a.merge_splits; ++sp) {
-        const size_t pi = p0 + (size_t)sp * G;
-        const float ms = a.part_ml[pi * 2];
-        const float sc = (ms == NEG_INF) ? 0.f : fast_exp2(ms - M2);
-        L = fmaf(a.part_ml[pi * 2 + 1], sc, L);
-        O = fmaf(a.part_o[pi * D + e], sc, O);
-      }
-      M = M2;
-    }
-    if (phase == 2 || (a.splits == 1 && phase == 0)) {
-      const size_t o = ((size_t)b * a.n_kv_heads * G + (size_t)h * G + g) * D + e;
-      store_out(a.out, o, L > 0.f ? O / L : 0.f, DT);
-      if (a.lse && e == 0) a.lse[(size_t)b * a.n_kv_heads * G + h * G + g] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : NEG_INF;
-    } else {
-      const size_t pidx = ((size_t)unit * a.splits + split) * G + g;
-      if (!OVERLAP && a.arrived) {       // read by another workgroup of this very launch
-        part_store<true>(a.part_o + pidx * D + e, O);
-        if (e == 0) {
-          part_store<true>(a.part_ml + pidx * 2, M);
-          part_store<true>(a.part_ml + pidx * 2 + 1, L);
-        }
-      } else {
-        a.part_o[pidx * D + e] = O;
-        if (e == 0) {
-          a.part_ml[pidx * 2] = M;
-          a.part_ml[pidx * 2 + 1] = L;
-        }
-      }
+    for (int kc = 0; kc < KC; ++kc) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (l16 < G) v = *(const u32x4*)(qp + kc * 64 + g4 * 16);
+      qb[kc] = __builtin_bit_cast(bf16x8_t, v);
     }
   }
-  if constexpr (!OVERLAP) {
-    // Several splits and a counter array: the workgroup that finds all the others of its unit done merges
-    // their partial results into the output, which saves the separate combine launch.  Every lane waits
-    // until its partial-result stores are acknowledged, the workgroup meets, one lane bumps the unit's
-    // counter; whoever reads splits - 1 there is the last arrival and does the merge.  Nobody waits for
-    // anybody else.  The last arrival puts the counter back to zero for the next launch.
-    if (a.splits > 1 && a.arrived != nullptr) {
-      __shared__ int s_last;
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-      wait_vector_memory();
-      __syncthreads();
-      if (tid == 0) {
-        const int before = __hip_atomic_fetch_add(a.arrived + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = before == a.splits - 1;
-      }
-      __syncthreads();
-      if (s_last) {
-        wait_vector_memory();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        if (a.splits <= 4) merge_arrived<DT, D, G, 4>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, a.splits);
-        else if (a.splits <= 8) merge_arrived<DT, D, G, 8>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, a.splits);
-        else combine_unit<DT, true>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, G, D, a.splits);
-        if (tid == 0) __hip_atomic_store(a.arrived + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
+  f32x4_t ot[NDT];
+#pragma unroll
+  for (int dt = 0; dt < NDT; ++dt) ot[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_run = NEG_INF, l_run = 0.f;   // head l16; l_run covers this lane's tokens only
+
+  // V^T tile of this wave.  Token 16 m + 4 q + j of a tile sits at position 8 q + 4 m + j of a row; the lane
+  // (r8, c8) holds tokens 2 r8 and 2 r8 + 1 (+ 16 m) of slice c8: one word at byte 16 (r8 / 2) + 8 m + 4 (r8 % 2)
+  // of row d, chunk index XORed with (d / 8) % 4 = c8 % 4.  Lanes with odd c8 write their odd column first,
+  // so that one store instruction touches rows of both parities (all 32 banks).
+  unsigned char* vt = s_buf + wave * kVt;
+  const int vchunk = ((r8 >> 1) ^ (c8 & 3)) * 16 + 4 * (r8 & 1);
+  unsigned char* vw_first = vt + (8 * c8 + (c8 & 1)) * 64 + vchunk;
+  unsigned char* vw_second = vt + (8 * c8 + 1 - (c8 & 1)) * 64 + vchunk;
+  const uint32_t sel_first = (c8 & 1) ? 0x07060302u : 0x05040100u;    // high (odd column) or low halves of two words
+  const uint32_t sel_second = (c8 & 1) ? 0x05040100u : 0x07060302u;
+  // operand reads: row d = 16 dt + l16, positions 8 g4 .. + 7 = chunk g4 ^ ((d / 8) % 4)
+  const unsigned char* vr0 = vt + l16 * 64 + ((g4 ^ (l16 >> 3)) * 16);          // tiles with (2 dt) % 4 == 0
+  const unsigned char* vr2 = vt + l16 * 64 + ((g4 ^ (l16 >> 3) ^ 2) * 16);      // tiles with (2 dt) % 4 == 2
+  __syncthreads();
+
+  const int total_tiles = n_sel * TPB;
+  const int t_begin = (int)(((long long)split * total_tiles) / a.splits);
+  const int t_end = (int)(((long long)(split + 1) * total_tiles) / a.splits);
+  constexpr size_t kBlockBytes = (size_t)kBlockTokens * ROWB;
+
+  for (int t = t_begin + wave; t < t_end; t += kWaves) {
+    const int i_blk = t / TPB;
+    const int part = t % TPB;
+    const int nvalid = s_valid[i_blk] - part * TILE;
+    if (nvalid <= 0) continue;
+    const size_t slot_lin = (size_t)unit * a.gpu_slots + s_slot[i_blk];
+    const char* kp = (const char*)a.pool_k + slot_lin * kBlockBytes + (size_t)(part * TILE + l16) * ROWB + g4 * 16;
+    const char* vp = (const char*)a.pool_v + slot_lin * kBlockBytes + (size_t)(part * TILE + 2 * r8) * ROWB + c8 * 16;
+
+    u32x4 kx[2][KC], vx[4][VPL];
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc)
+        kx[m][kc] = __builtin_nontemporal_load((const u32x4*)(kp + (size_t)m * 16 * ROWB + kc * 64));
+    f32x4_t bz[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
+    if (a.pool_bias != nullptr) {
+      const float* bp = a.pool_bias + slot_lin * kBlockTokens + part * TILE + 4 * g4;
+      bz[0] = __builtin_nontemporal_load((const f32x4_t*)bp);
+      bz[1] = __builtin_nontemporal_load((const f32x4_t*)(bp + 16));
     }
-    if (a.trace && tid == 0) {   // when and where this workgroup ran: start, end, XCD (hardware register XCC_ID), its index
-      unsigned long long* t = a.trace + (size_t)blockIdx.x * 4;
-      t[0] = t_start;
-      t[1] = __builtin_amdgcn_s_memrealtime();
-      t[2] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 0xfu;
-      t[3] = blockIdx.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)     // token 2 r8 + (i & 1) + 16 (i >> 1)
+#pragma unroll
+      for (int v = 0; v < VPL; ++v)
+        vx[i][v] = __builtin_nontemporal_load((const u32x4*)(vp + (size_t)((i & 1) + 16 * (i >> 1)) * ROWB + v * 128));
+
+    // scores: st[m][j] = token 16 m + 4 g4 + j, head l16
+    f32x4_t st[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+      for (int m = 0; m < 2; ++m)
+        st[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kx[m][kc]), qb[kc], st[m], 0, 0, 0);
+
+    float z[2][4];
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) z[m][j] = fmaf(st[m][j], a.scale_log2e, bz[m][j] * kLog2e);
+    const bool masked = nvalid < TILE;   // wave-uniform: only the partial tail block takes this path
+    if (masked) {
+#pragma unroll
+      for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (16 * m + 4 * g4 + j >= nvalid) z[m][j] = NEG_INF;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)        // stale bytes beyond T must not reach the sum
+        if (2 * r8 + (i & 1) + 16 * (i >> 1) >= nvalid)
+#pragma unroll
+          for (int v = 0; v < VPL; ++v) vx[i][v] = u32x4{0u, 0u, 0u, 0u};
+    }
+    float mt = fmaxf(fmaxf(fmaxf(z[0][0], z[0][1]), fmaxf(z[0][2], z[0][3])),
+                     fmaxf(fmaxf(z[1][0], z[1][1]), fmaxf(z[1][2], z[1][3])));
+    mt = head_max(mt);
+    const float m_new = fmaxf(m_run, mt);
+    if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0ull) {
+      const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
+      const float alpha = fast_exp2(m_run - m_use);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < NDT; ++dt) ot[dt] *= alpha;
+    }
+    const float m_use = (m_run == NEG_INF) ? 0.f : m_run;
+    float p[2][4];
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        p[m][j] = fast_exp2(z[m][j] - m_use);
+        l_run += p[m][j];
+      }
+    const u32x4 pw = {pack2_bf16(p[0][0], p[0][1]), pack2_bf16(p[0][2], p[0][3]), pack2_bf16(p[1][0], p[1][1]),
+                      pack2_bf16(p[1][2], p[1][3])};   // positions 8 g4 + 4 m + j
+    const bf16x8_t pb = __builtin_bit_cast(bf16x8_t, pw);
+
+    // V^T into LDS
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int v = 0; v < VPL; ++v)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const uint32_t lo = vx[2 * m][v][w], hi = vx[2 * m + 1][v][w];   // tokens t and t + 1, columns 2 w and 2 w + 1 of the slice
+          const int off = (64 * v + 2 * w) * 64 + 8 * m;
+          *(uint32_t*)(vw_first + off) = __builtin_amdgcn_perm(hi, lo, sel_first);
+          *(uint32_t*)(vw_second + off) = __builtin_amdgcn_perm(hi, lo, sel_second);
+        }
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt) {
+      const unsigned char* rp = ((2 * dt) & 2) ? vr2 : vr0;
+      const bf16x8_t av = *(const bf16x8_t*)(rp + dt * 16 * 64);
+      ot[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb, ot[dt], 0, 0, 0);
     }
   }
+
+  // the wave's result: O^T values are complete sums; only l is spread over the four lanes of a head
+  float l_tot = l_run + __shfl_xor(l_run, 16);
+  l_tot += __shfl_xor(l_tot, 32);
+  __syncthreads();     // every wave is done with its V^T tile: the buffer now takes the waves' O
+  if (l16 < G) {
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+      *(f32x4_t*)(&s_acc[wave][l16][16 * dt + 4 * g4]) = ot[dt];
+    if (g4 == 0) {
+      s_m[wave][l16] = m_run;
+      s_l[wave][l16] = l_tot;
+    }
+  }
+  __syncthreads();
+  decode_finish<DT, D, G, OVERLAP>(a, phase, unit, split, b, h, tid, s_m, s_l, s_acc, t_start);
 }
 
 // One workgroup per unit: merges the split partial results with log-sum-exp weights.
@@ -570,6 +818,19 @@ __global__ __launch_bounds__(kThreads) void decode_combine_kernel(const float* _
                                                                   const float* __restrict__ part_ml, void* out,
                                                                   float* lse, int n_kv_heads, int G, int D, int splits) {
   combine_unit<DT, false>(part_o, part_ml, out, lse, blockIdx.x, n_kv_heads, G, D, splits);
+}
+
+template <int D, bool OVERLAP>
+bool dispatch_mfma(int g, const DecodeArgs& a, dim3 grid, hipStream_t s) {
+#define NOSA_CASE(GG)                                                                                    \
+  case GG:                                                                                               \
+    hipLaunchKernelGGL((decode_mfma_kernel<D, GG, OVERLAP>), grid, dim3(kThreads), 0, s, a);             \
+    return true;
+  switch (g) {
+    NOSA_CASE(1) NOSA_CASE(2) NOSA_CASE(3) NOSA_CASE(4) NOSA_CASE(6) NOSA_CASE(8) NOSA_CASE(12) NOSA_CASE(16)
+    default: return false;
+  }
+#undef NOSA_CASE
 }
 
 template <int DT, int D, bool OVERLAP>
@@ -668,8 +929,17 @@ bool dispatch_dim(int D, int G, const DecodeArgs& a, dim3 grid, hipStream_t s) {
   return D == 128 ? dispatch_group<DT, 128, OVERLAP>(G, a, grid, s) : dispatch_group<DT, 64, OVERLAP>(G, a, grid, s);
 }
 
+// Which kernel attends: the matrix-core one for bf16 unless the context asks for the vector kernel
+// (attention_kernel 1); the vector kernel for fp32.
+bool decode_uses_matrix_cores(const nosa_ctx* ctx) {
+  return ctx->p.dtype == NOSA_DTYPE_BF16 && ctx->attention_kernel != 1;
+}
+
 template <bool OVERLAP>
-bool dispatch(const nosa_params& p, int G, const DecodeArgs& a, dim3 grid, hipStream_t s) {
+bool dispatch(const nosa_ctx* ctx, int G, const DecodeArgs& a, dim3 grid, hipStream_t s) {
+  const nosa_params& p = ctx->p;
+  if (decode_uses_matrix_cores(ctx))
+    return p.head_dim == 128 ? dispatch_mfma<128, OVERLAP>(G, a, grid, s) : dispatch_mfma<64, OVERLAP>(G, a, grid, s);
   return p.dtype == NOSA_DTYPE_BF16 ? dispatch_dim<NOSA_DTYPE_BF16, OVERLAP>(p.head_dim, G, a, grid, s)
                                     : dispatch_dim<NOSA_DTYPE_F32, OVERLAP>(p.head_dim, G, a, grid, s);
 }
@@ -704,7 +974,7 @@ int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* 
     a.phase = 1;
     {
       TimedLaunch tl(ctx, NOSA_KERNEL_DECODE, ctx->main);
-      NOSA_REQUIRE(ctx, dispatch<true>(p, G, a, dim3(S * ctx->units), ctx->main), NOSA_ESHAPE, "GQA group %d unsupported", G);
+      NOSA_REQUIRE(ctx, dispatch<true>(ctx, G, a, dim3(S * ctx->units), ctx->main), NOSA_ESHAPE, "GQA group %d unsupported", G);
     }
     NOSA_HIP(ctx, hipGetLastError());
     NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, wait_fetch, 0));
@@ -713,7 +983,7 @@ int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* 
     a.splits = 1;
     {
       TimedLaunch tl(ctx, NOSA_KERNEL_COMBINE, ctx->main);
-      NOSA_REQUIRE(ctx, dispatch<true>(p, G, a, dim3(ctx->units), ctx->main), NOSA_ESHAPE, "GQA group %d unsupported", G);
+      NOSA_REQUIRE(ctx, dispatch<true>(ctx, G, a, dim3(ctx->units), ctx->main), NOSA_ESHAPE, "GQA group %d unsupported", G);
     }
     NOSA_HIP(ctx, hipGetLastError());
     return NOSA_OK;
@@ -721,7 +991,7 @@ int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* 
   if (wait_fetch) NOSA_HIP(ctx, hipStreamWaitEvent(ctx->main, wait_fetch, 0));
   {
     TimedLaunch tl(ctx, NOSA_KERNEL_DECODE, ctx->main);
-    NOSA_REQUIRE(ctx, dispatch<false>(p, G, a, dim3(S * ctx->units), ctx->main), NOSA_ESHAPE, "GQA group %d unsupported", G);
+    NOSA_REQUIRE(ctx, dispatch<false>(ctx, G, a, dim3(S * ctx->units), ctx->main), NOSA_ESHAPE, "GQA group %d unsupported", G);
   }
   NOSA_HIP(ctx, hipGetLastError());
   if (S > 1 && !a.arrived) {

@@ -41,6 +41,7 @@ struct nosa_ctx {
   const int32_t* pending_load_list = nullptr;   // arguments of the fetch in flight (caller-owned, dev)
   const int32_t* pending_n_load = nullptr;
   int overlap = 1;
+  int attention_kernel = 0; // 0 chosen from the shape, 1 vector-ALU kernel, 2 matrix-core kernel (bf16, G in {4,6,8,12,16})
   int merge_in_kernel = 1;  // split attention: the last workgroup of a unit merges (0: a separate combine launch)
   int fuse_stage1 = 1;      // nosa_decode_step runs scores + selection as one kernel when the shape allows
   int splits = 1;

