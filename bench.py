@@ -54,6 +54,8 @@ def parse_args():
                     help="run block score and selection as two kernels inside nosa_decode_step (default: one kernel, scores stay on chip)")
     ap.add_argument("--attention-kernel", type=int, default=0, choices=[0, 1, 2],
                     help="0 chosen from the shape, 1 vector-ALU attention kernel, 2 matrix-core attention kernel (bf16)")
+    ap.add_argument("--gap-cycles", type=int, default=0,
+                    help="experiment: a one-thread spin kernel of this many clock ticks before every step (the GPU is as good as idle meanwhile)")
     ap.add_argument("--no-larger-pool", action="store_true",
                     help="skip the second measurement of the headline workload with C = 96 slots and importance-ranked victims")
     ap.add_argument("--locality-steps", type=int, default=64, help="untimed steps after the timed regions that record the miss count of every step")
@@ -654,6 +656,8 @@ def measure(args, w):
     q_static = [torch.zeros_like(queries[0][0]) for _ in range(L)] if args.mode == "graph" else None
 
     def do_step(l, q):
+        if args.gap_cycles:                         # experiment: an almost idle GPU for a while before every step
+            torch.cuda._sleep(args.gap_cycles)
         if args.mode == "calls":
             layers[l].step(q)
         elif args.mode == "fused":
@@ -756,7 +760,7 @@ def measure(args, w):
     # kernel on this workload, not taken during this run (counters need the profiler attached)
     traffic, traffic_source = None, None
     tfile = os.path.join(ROOT, "profiles", f"sparse_decode_{w.name}_hbm_traffic.json")
-    if os.path.exists(tfile) and w.gpu_slots == CONFIGS[w.name].gpu_slots:
+    if os.path.exists(tfile) and w == CONFIGS[w.name] and args.attention_kernel != 1:
         with open(tfile) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
         traffic_source = f"profiles/sparse_decode_{w.name}_hbm_traffic.md (rocprofv3 --pmc run of this command, stored; not measured in this run)"
@@ -776,7 +780,9 @@ def measure(args, w):
                    "gpu_slots": w.gpu_slots, "victim_policy": w.victim_policy, "layers_cycled": L,
                    "stage1": "two kernels" if (args.no_fused_select or args.mode == "calls") else "one kernel (scores + selection + load positions)", "host_pools": LH, "splits": ctx.splits, "step_entry": args.mode,
                    "fetch": "resident (no misses)" if args.resident else "main stream (every kernel alone)"},
-        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel<bf16,128,4,false>" if w.name == "8b" else "decode_partial_kernel",
+        "roofline": {"bound": "hbm", "kernel": (f"decode_mfma_kernel<{w.head_dim},{w.group},false> (matrix-core attention)"
+                                                if w.dtype == "bf16" and args.attention_kernel != 1 else
+                                                f"decode_partial_kernel<{w.dtype},{w.head_dim},{w.group},false> (vector-ALU attention)"),
                      "achieved": achieved, "peak": peak, "unit": "GB/s",
                      "frac": (achieved / peak) if achieved else None, "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes_per_launch": dec_bytes, "avg_launch_us": dec_us,

@@ -4,6 +4,9 @@
 // paged pool.  A block's keys and values are contiguous 8-32 KiB pieces, so every wave-load is a
 // 1 KiB contiguous read; all loads of a piece are issued before the first store so that many
 // requests are in flight on the link.  The list lengths live on the device; nothing is read back.
+// The stores into the pool are non-temporal: written normally, the 80 MB of a step at the 8B shape stay
+// behind as dirty lines in the L2s and the memory-side cache, and their write-back then competes with the
+// reads of the attention kernel that follows (measured: 179 us instead of 163 us for that kernel).
 #include "nosa_device.h"
 #include "nosa_internal.h"
 
@@ -42,7 +45,7 @@ __device__ __forceinline__ void copy_piece(const u32x4* __restrict__ src, u32x4*
 #pragma unroll
     for (int i = 0; i < kInFlight; ++i) {
       const int x = base + i * kThreads + tid;
-      if (x < nvec) dst[x] = buf[i];
+      if (x < nvec) __builtin_nontemporal_store(buf[i], dst + x);
     }
   }
 }
@@ -116,8 +119,8 @@ __global__ __launch_bounds__(kThreads) void fetch_tokens_kernel(const TokenFetch
       for (int i = 0; i < kInFlight; ++i) {
         if (dst[i] < 0) continue;
         const size_t d = ((size_t)unit * a.gpu_rows + dst[i]);
-        a.pool_k[d * lpr + cc] = kb[i];
-        a.pool_v[d * lpr + cc] = vb[i];
+        __builtin_nontemporal_store(kb[i], a.pool_k + d * lpr + cc);
+        __builtin_nontemporal_store(vb[i], a.pool_v + d * lpr + cc);
         if (a.host_bias && cc == 0) a.pool_bias[d] = bb[i];
       }
     }
