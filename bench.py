@@ -355,6 +355,7 @@ def xcd_study(args):
                               n_sub_max=w.n_sub_max, dtype=w.dtype)
     ctx = nosa.Nosa(params, device=dev)
     ctx.set_overlap(False)
+    ctx.set_attention_kernel(args.attention_kernel)
     if args.splits:
         ctx.set_splits(args.splits)
     lay = make_layer(w, args.seed, 0, device=dev)
@@ -413,7 +414,7 @@ def xcd_study(args):
                           "round_robin_matches_xcc_id": bool(((np.arange(n_wg) % 8) == xcds).all()), "by_xcd": by})
     ctx.set_trace(None)
     ctx.close()
-    print(json.dumps({"study": "xcd", "workload": w.name, "workgroups": n_wg, "splits": n_wg // w.units, "visits_averaged": visits,
+    print(json.dumps({"study": "xcd", "workload": w.name, "attention_kernel": "vector" if args.attention_kernel == 1 else "matrix-core", "workgroups": n_wg, "splits": n_wg // w.units, "visits_averaged": visits,
                       "layers": per_layer}), flush=True)
 
 
