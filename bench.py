@@ -781,7 +781,7 @@ def measure(args, w):
                    "gpu_slots": w.gpu_slots, "victim_policy": w.victim_policy, "layers_cycled": L,
                    "stage1": "two kernels" if (args.no_fused_select or args.mode == "calls") else "one kernel (scores + selection + load positions)", "host_pools": LH, "splits": ctx.splits, "step_entry": args.mode,
                    "fetch": "resident (no misses)" if args.resident else "main stream (every kernel alone)"},
-        "roofline": {"bound": "hbm", "kernel": (f"decode_mfma_kernel<{w.head_dim},{w.group},false> (matrix-core attention)"
+        "roofline": {"bound": "hbm", "kernel": (f"decode_mfma_kernel<{w.head_dim},false> (matrix-core attention, group {w.group})"
                                                 if w.dtype == "bf16" and args.attention_kernel != 1 else
                                                 f"decode_partial_kernel<{w.dtype},{w.head_dim},{w.group},false> (vector-ALU attention)"),
                      "achieved": achieved, "peak": peak, "unit": "GB/s",

@@ -110,7 +110,10 @@ int nosa_get_splits(const nosa_ctx* ctx);
  * G = 1 and for the G = 16 of the paper's own 3B and 8B models (32 query / 2 KV heads).
  * 1, the vector-ALU kernel (fp32 and bf16): K and V stream through registers in full lines, q.k by packed dot
  * products, P.V by fp32 FMAs; 4 G flops per byte, so it falls behind from G = 6 on and spills at G = 16.
- * 0 (default): 2 for bf16, 1 for fp32.  A request for 2 on an fp32 context runs 1.                      */
+ * 0 (default): 2 for bf16, 1 for fp32.  A request for 2 on an fp32 context runs 1.
+ * Group sizes G = Hq / Hkv: kernel 2 takes the group as an argument, any G in 1..16; kernel 1 is
+ * instantiated for G in {1, 2, 3, 4, 6, 8, 12, 16}.  So bf16 contexts accept every G up to 16 (a request
+ * for kernel 1 with another G runs 2), fp32 contexts the listed ones; nosa_validate_params says which. */
 int nosa_set_attention_kernel(nosa_ctx* ctx, int which);
 
 /* With several splits, who merges the partial results of a unit: 1 (default) the workgroup of the

@@ -65,8 +65,8 @@ static int validate(const nosa_params* p, char* msg, size_t len) {
   if (p->victim_policy != 0 && p->victim_policy != 1) return fail(NOSA_EINVAL, "unknown victim_policy %d", p->victim_policy);
   if (p->head_dim != 64 && p->head_dim != 128) return fail(NOSA_ESHAPE, "head_dim %d not in {64, 128}", p->head_dim);
   if (p->block_size != nosa::kBlockTokens) return fail(NOSA_ESHAPE, "block_size %d unsupported (64 only)", p->block_size);
-  if (!nosa::decode_supports_group(p->n_q_heads / p->n_kv_heads))
-    return fail(NOSA_ESHAPE, "GQA group %d unsupported (1, 2, 3, 4, 6, 8, 12, 16)", p->n_q_heads / p->n_kv_heads);
+  if (!nosa::decode_supports_group(p->n_q_heads / p->n_kv_heads, p->dtype))
+    return fail(NOSA_ESHAPE, "GQA group %d unsupported (bf16: 1..16; fp32: 1, 2, 3, 4, 6, 8, 12, 16)", p->n_q_heads / p->n_kv_heads);
   if (p->pool_kernel < 1 || p->pool_stride < 1 || p->pool_kernel > p->block_size)
     return fail(NOSA_EINVAL, "pool_kernel (%d) must be in [1, block_size], pool_stride (%d) >= 1", p->pool_kernel,
                 p->pool_stride);

@@ -1,21 +1,28 @@
 // Block-sparse decode attention over the selected blocks of the paged GPU pool
-// (output Eq. of Sec. 3.1 "Attention Calculation"; Alg. 1 Stage 2), as split partial results
-// plus a combine pass.
+// (output Eq. of Sec. 3.1 "Attention Calculation"; Alg. 1 Stage 2).
 //
-// The work is a stream over K and V rows (4 flop per byte): it is HBM-bound, so the kernel is
-// organised around wide coalesced loads, not around matrix cores.
+// The work is a stream over K and V rows, each read once: the bound is HBM.  Two kernels share the
+// launch geometry, the block table, the split bookkeeping and the merge (decode_work_table,
+// decode_finish):
+//
+//  * decode_mfma_kernel (bf16, the default there).  Per byte of K and V there are 4 G flops (G = query
+//    heads per KV head); from G = 6 on the vector ALUs cannot keep up with HBM, and the paper's own 3B
+//    and 8B models have G = 16.  The heads of a group are one dimension of v_mfma_f32_16x16x32_bf16,
+//    so the cost of the two products no longer depends on G and the kernel streams at the same rate
+//    for every group size.  Described at the kernel.
+//  * decode_partial_kernel (fp32 and bf16), vector ALUs only, described next.
 //
 // Mapping.  One workgroup (4 wavefronts) handles one (unit, split): a contiguous range of the
-// unit's tiles, a tile being 8 wave-loads (8 KiB) of K and as many of V from one selected block.
-// In a wave-load every lane reads 16 bytes; 8 adjacent lanes cover one 128-byte line of a token
-// row, so one instruction reads whole lines of 8 rows, and VPL = row_bytes / 128 instructions
-// read the 8 rows completely ("a step").  A lane keeps the slices of q it needs in registers (all
-// G heads of the group), forms partial dot products, and the 8 lanes of a row add them up with
-// three DPP row operations (no LDS).  The row's scores then sit in exactly the lanes that hold the
-// matching slices of the V row, so the P.V update needs no data movement either.  Each of the 8
+// unit's tiles.  In the vector kernel a tile is 8 wave-loads (8 KiB) of K and as many of V from one
+// selected block.  In a wave-load every lane reads 16 bytes; 8 adjacent lanes cover one 128-byte line
+// of a token row, so one instruction reads whole lines of 8 rows, and VPL = row_bytes / 128
+// instructions read the 8 rows completely ("a step").  A lane keeps the slices of q it needs in
+// registers (all G heads of the group), forms partial dot products, and the 8 lanes of a row add them
+// up with three DPP row operations (no LDS).  The row's scores then sit in exactly the lanes that hold
+// the matching slices of the V row, so the P.V update needs no data movement either.  Each of the 8
 // row-groups of lanes carries its own online-softmax state (m, l, acc[G][slices]); states are
 // merged once at the end: across row-groups by lane exchange, across waves through LDS, across
-// splits by the combine kernel.
+// splits by the last workgroup of the unit to finish (or by the combine kernel).
 //
 // Logits are kept in the log2 domain: z' = (scale*log2 e) q.k + b*log2 e, p = 2^(z' - m').
 #include <cmath>
@@ -65,7 +72,7 @@ struct DecodeArgs {
   float* lse;
   const int32_t* load_list;   // phases 1 and 2: the (block, slot) pairs of the fetch in flight
   const int32_t* n_load;
-  int n_kv_heads, gpu_slots, k_blocks, max_blocks, splits;
+  int n_kv_heads, group, gpu_slots, k_blocks, max_blocks, splits;
   int phase;         // 0: all selected blocks; 1: only blocks not in load_list; 2: only load_list, then merge
   int merge_splits;  // phase 2: number of phase-1 partial results per unit to merge into the output
   float scale_log2e;
@@ -187,10 +194,9 @@ __device__ __forceinline__ void combine_unit(const float* part_o, const float* p
 // splits for each of its output elements -- is requested before the first one is used, so the merge pays
 // one round trip to memory instead of one per split.  Splits beyond `splits` contribute m = -inf, l = 0:
 // a term of weight zero.
-template <int DT, int D, int G, int SMAX>
+template <int DT, int D, int NI, int SMAX>
 __device__ __forceinline__ void merge_arrived(const float* part_o, const float* part_ml, void* out, float* lse, int unit,
-                                              int n_kv_heads, int splits) {
-  constexpr int NI = (G * D + kThreads - 1) / kThreads;
+                                              int n_kv_heads, int G, int splits) {
   const int b = unit / n_kv_heads, h = unit % n_kv_heads;
   float ms[NI][SMAX], ls[NI][SMAX], os[NI][SMAX];
 #pragma unroll
@@ -285,10 +291,12 @@ __device__ __forceinline__ int decode_work_table(const DecodeArgs& a, const int 
 // Last part of an attention workgroup: the per-wave states (m in the log2 domain, l, un-normalised O) that the
 // waves left in LDS are merged; the result is the output (one split, or phase 2, which also folds in the
 // phase-1 partial results), or a partial result, which the last workgroup of the unit to arrive merges.
-template <int DT, int D, int G, bool OVERLAP>
+// GS = heads the LDS arrays are laid out for (row stride), G = heads of the group (<= GS; a compile-time constant
+// at the vector kernel's call site, a kernel argument at the matrix-core kernel's).
+template <int DT, int D, int GS, bool OVERLAP>
 __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const int phase, const int unit, const int split,
-                                              const int b, const int h, const int tid, const float (*s_m)[G],
-                                              const float (*s_l)[G], const float (*s_acc)[G][D],
+                                              const int b, const int h, const int tid, const int G,
+                                              const float (*s_m)[GS], const float (*s_l)[GS], const float (*s_acc)[GS][D],
                                               const unsigned long long t_start) {
   constexpr float NEG_INF = -INFINITY;
   // ---- merge the waves; write the partial result (or the output when there is one split) ----
@@ -362,10 +370,15 @@ __device__ __forceinline__ void decode_finish(const DecodeArgs& a, const int pha
         wait_vector_memory();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         // all partial values in flight at once while that fits the registers: (outputs per lane) x (splits) x 3
-        constexpr int kPerLane = (G * D + kThreads - 1) / kThreads;
-        if (a.splits <= 4 && kPerLane <= 8) merge_arrived<DT, D, G, 4>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, a.splits);
-        else if (a.splits <= 8 && kPerLane <= 4) merge_arrived<DT, D, G, 8>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, a.splits);
-        else combine_unit<DT, true>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, G, D, a.splits);
+        constexpr int kPerLaneMax = (GS * D + kThreads - 1) / kThreads;
+        constexpr int kPerLane8 = kPerLaneMax < 8 ? kPerLaneMax : 8, kPerLane4 = kPerLaneMax < 4 ? kPerLaneMax : 4;
+        const int per_lane = (G * D + kThreads - 1) / kThreads;
+        if (a.splits <= 4 && per_lane <= kPerLane8)
+          merge_arrived<DT, D, kPerLane8, 4>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, G, a.splits);
+        else if (a.splits <= 8 && per_lane <= kPerLane4)
+          merge_arrived<DT, D, kPerLane4, 8>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, G, a.splits);
+        else
+          combine_unit<DT, true>(a.part_o, a.part_ml, a.out, a.lse, unit, a.n_kv_heads, G, D, a.splits);
         if (tid == 0) __hip_atomic_store(a.arrived + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
@@ -585,7 +598,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
   }
   __syncthreads();
 
-  decode_finish<DT, D, G, OVERLAP>(a, phase, unit, split, b, h, tid, s_m, s_l, s_acc, t_start);
+  decode_finish<DT, D, G, OVERLAP>(a, phase, unit, split, b, h, tid, G, s_m, s_l, s_acc, t_start);
 }
 
 // ---- the same attention on the matrix cores, for large query groups ------------------------------------
@@ -622,9 +635,12 @@ __device__ __forceinline__ float head_max(float x) {
   return fmaxf(x, __shfl_xor(x, 32));
 }
 
-template <int D, int G, bool OVERLAP>
+constexpr int kHeadTile = 16;   // heads per matrix-core tile: the largest group the kernel takes
+
+template <int D, bool OVERLAP>
 __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeArgs a) {
   constexpr int DT = NOSA_DTYPE_BF16;
+  const int G = a.group;                 // 1 .. 16 heads per KV head
   constexpr int KC = D / 32;             // k-steps of the score product
   constexpr int NDT = D / 16;            // 16-row tiles of O^T
   constexpr int ROWB = D * 2;            // bytes per K or V row
@@ -634,16 +650,15 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeArgs 
   constexpr int kVt = D * 64;            // bytes of one wave's V^T tile: D rows x 32 positions x 2 B
   constexpr float NEG_INF = -INFINITY;
   constexpr float kLog2e = 1.4426950408889634f;
-  static_assert(G <= 16, "the heads of a group are the 16 columns of one matrix-core tile");
   const int phase = OVERLAP ? a.phase : 0;
 
   __shared__ int s_slot[kMaxSelBlocks];
   __shared__ int s_valid[kMaxSelBlocks];
-  __shared__ float s_m[kWaves][G];
-  __shared__ float s_l[kWaves][G];
+  __shared__ float s_m[kWaves][kHeadTile];
+  __shared__ float s_l[kWaves][kHeadTile];
   __shared__ __align__(16) unsigned char s_buf[kWaves * kVt];   // V^T tiles in the loop, the waves' O afterwards
-  static_assert(sizeof(float) * kWaves * G * D <= sizeof(s_buf), "the per-wave results must fit the tile buffer");
-  float (*s_acc)[G][D] = reinterpret_cast<float (*)[G][D]>(s_buf);
+  static_assert(sizeof(float) * kWaves * kHeadTile * D <= sizeof(s_buf), "the per-wave results must fit the tile buffer");
+  float (*s_acc)[kHeadTile][D] = reinterpret_cast<float (*)[kHeadTile][D]>(s_buf);
 
   const int unit = blockIdx.x / a.splits;
   const int split = blockIdx.x % a.splits;
@@ -809,7 +824,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeArgs 
     }
   }
   __syncthreads();
-  decode_finish<DT, D, G, OVERLAP>(a, phase, unit, split, b, h, tid, s_m, s_l, s_acc, t_start);
+  decode_finish<DT, D, kHeadTile, OVERLAP>(a, phase, unit, split, b, h, tid, G, s_m, s_l, s_acc, t_start);
 }
 
 // One workgroup per unit: merges the split partial results with log-sum-exp weights.
@@ -822,15 +837,9 @@ __global__ __launch_bounds__(kThreads) void decode_combine_kernel(const float* _
 
 template <int D, bool OVERLAP>
 bool dispatch_mfma(int g, const DecodeArgs& a, dim3 grid, hipStream_t s) {
-#define NOSA_CASE(GG)                                                                                    \
-  case GG:                                                                                               \
-    hipLaunchKernelGGL((decode_mfma_kernel<D, GG, OVERLAP>), grid, dim3(kThreads), 0, s, a);             \
-    return true;
-  switch (g) {
-    NOSA_CASE(1) NOSA_CASE(2) NOSA_CASE(3) NOSA_CASE(4) NOSA_CASE(6) NOSA_CASE(8) NOSA_CASE(12) NOSA_CASE(16)
-    default: return false;
-  }
-#undef NOSA_CASE
+  if (g < 1 || g > kHeadTile) return false;
+  hipLaunchKernelGGL((decode_mfma_kernel<D, OVERLAP>), grid, dim3(kThreads), 0, s, a);
+  return true;
 }
 
 template <int DT, int D, bool OVERLAP>
@@ -905,8 +914,13 @@ int decode_zero_counters(nosa_ctx* ctx, void* ws) {
   return NOSA_OK;
 }
 
-bool decode_supports_group(int g) {
+static bool vector_kernel_has_group(int g) {
   return g == 1 || g == 2 || g == 3 || g == 4 || g == 6 || g == 8 || g == 12 || g == 16;
+}
+
+// bf16: any group of 1..16 heads (matrix-core kernel); fp32: the groups the vector kernel is instantiated for
+bool decode_supports_group(int g, int dtype) {
+  return dtype == NOSA_DTYPE_BF16 ? (g >= 1 && g <= kHeadTile) : vector_kernel_has_group(g);
 }
 
 int decode_default_splits(const nosa_params& p) {
@@ -932,7 +946,8 @@ bool dispatch_dim(int D, int G, const DecodeArgs& a, dim3 grid, hipStream_t s) {
 // Which kernel attends: the matrix-core one for bf16 unless the context asks for the vector kernel
 // (attention_kernel 1); the vector kernel for fp32.
 bool decode_uses_matrix_cores(const nosa_ctx* ctx) {
-  return ctx->p.dtype == NOSA_DTYPE_BF16 && ctx->attention_kernel != 1;
+  if (ctx->p.dtype != NOSA_DTYPE_BF16) return false;
+  return ctx->attention_kernel != 1 || !vector_kernel_has_group(ctx->group);   // odd groups exist on the matrix cores only
 }
 
 template <bool OVERLAP>
@@ -965,7 +980,7 @@ int launch_decode(nosa_ctx* ctx, const void* q, const void* pool_k, const void* 
   a.trace = (ctx->trace && ctx->trace_capacity >= S * ctx->units) ? ctx->trace : nullptr;
   a.out = out; a.lse = lse;
   a.load_list = load_list; a.n_load = n_load;
-  a.n_kv_heads = p.n_kv_heads; a.gpu_slots = p.gpu_slots; a.k_blocks = p.k_blocks; a.max_blocks = p.max_blocks;
+  a.n_kv_heads = p.n_kv_heads; a.group = G; a.gpu_slots = p.gpu_slots; a.k_blocks = p.k_blocks; a.max_blocks = p.max_blocks;
   a.splits = S;
   a.phase = 0;
   a.merge_splits = 0;

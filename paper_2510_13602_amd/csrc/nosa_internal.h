@@ -127,7 +127,7 @@ int launch_split_qkv_evict(nosa_ctx* ctx, const void* qkv, const float* w1, cons
 int launch_fetch_tokens(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const void* host_v, const float* host_bias,
                         void* pool_k, void* pool_v, float* pool_bias, const int32_t* token_list, const int32_t* n_list,
                         int max_list);
-bool decode_supports_group(int g);
+bool decode_supports_group(int g, int dtype);
 int decode_default_splits(const nosa_params& p);
 
 }  // namespace nosa

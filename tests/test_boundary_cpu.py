@@ -36,6 +36,8 @@ def _good(**kw):
 def test_params_struct_matches_header_layout():
     assert ctypes.sizeof(nosa.Params) == 17 * 4
     nosa.validate_params(_good())
+    nosa.validate_params(_good(n_q_heads=10))           # bf16: any group of 1..16 heads
+    nosa.validate_params(_good(n_q_heads=14))
     assert nosa.load_library().nosa_workspace_bytes(_good()) >= 4 * 2 * 16 * 4 * 130 * 4
 
 
@@ -43,7 +45,8 @@ def test_params_struct_matches_header_layout():
     (dict(head_dim=96), nosa.binding.NOSA_ESHAPE),
     (dict(block_size=32), nosa.binding.NOSA_ESHAPE),
     (dict(n_q_heads=7), nosa.binding.NOSA_EINVAL),
-    (dict(n_q_heads=10), nosa.binding.NOSA_ESHAPE),          # group 5 has no kernel
+    (dict(n_q_heads=10, dtype="fp32"), nosa.binding.NOSA_ESHAPE),   # group 5: bf16 only (matrix-core kernel)
+    (dict(n_q_heads=34), nosa.binding.NOSA_ESHAPE),          # group 17: more heads than one matrix-core tile
     (dict(kq_blocks=60), nosa.binding.NOSA_ESHAPE),          # sink + window + kq > K
     (dict(gpu_slots=32), nosa.binding.NOSA_ESHAPE),          # C < K
     (dict(window_blocks=0), nosa.binding.NOSA_EINVAL),

@@ -159,6 +159,12 @@ MATRIX_CASES = [
     (128, 2, 2, 12, 20, 5, 3, True),             # group 1
     (64, 4, 2, 12, 20, 47, None, True),          # group 2
     (128, 3, 1, 7, 10, 62, 2, False),            # group 3
+    # groups the vector kernel has no instantiation for (the matrix-core kernel takes the group as an argument)
+    (128, 28, 4, 16, 30, 21, None, True),        # group 7 (28 query heads over 4 KV heads)
+    (128, 10, 2, 12, 20, 40, 3, True),           # group 5
+    (64, 9, 1, 6, 9, 7, 4, True),                # d 64, group 9
+    (128, 13, 1, 7, 10, 62, 16, False),          # group 13, more splits than outputs per lane allow in registers
+    (64, 30, 2, 12, 20, 47, 2, True),            # d 64, group 15
 ]
 
 

@@ -27,6 +27,7 @@ pytestmark = pytest.mark.gpu
     ("overlapping_pool_windows", dict(n_q_heads=8, n_kv_heads=2, head_dim=128, k_blocks=8, kq_blocks=2, window_blocks=2,
                                       pool_kernel=32, pool_stride=16), 64 * 6, 64 * 4),
     ("d128_g16", dict(n_q_heads=16, n_kv_heads=1, head_dim=128, k_blocks=7, kq_blocks=2, window_blocks=2), 64 * 7, 64 * 2),
+    ("d128_g7", dict(n_q_heads=14, n_kv_heads=2, head_dim=128, k_blocks=8, kq_blocks=2, window_blocks=2), 64 * 6, 64 * 3),
     ("budget_covers_all", dict(n_q_heads=8, n_kv_heads=2, head_dim=128, k_blocks=10, kq_blocks=4, window_blocks=2), 0, 64 * 8),
 ])
 def test_prefill_parity(name, kw, p0, lq):

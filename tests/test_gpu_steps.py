@@ -27,6 +27,18 @@ def test_tiny_ragged_context_serial_order():
     run_parity(w, seed=1, steps=6, overlap=False)
 
 
+@pytest.mark.parametrize("d,hq,hkv", [(128, 28, 4), (64, 10, 2), (128, 15, 1)])
+def test_steps_with_group_sizes_of_seven_five_fifteen(d, hq, hkv):
+    """bf16 groups that are no power of two or multiple of three (28 query heads over 4 KV heads is a common layout):
+    whole steps with the side-stream fetch, growing context included."""
+    from helpers import small_workload
+    from pipeline import run_growing
+    w = small_workload(batch=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, context=64 * 40 + 11, k_blocks=12, kq_blocks=3,
+                       window_blocks=2, gpu_slots=14, dtype="bf16", structure="planted", generated=70)
+    run_parity(w, seed=hq, steps=5, overlap=True)
+    run_growing(w, hq + 1, 66)
+
+
 def test_1b_shaped_half_resident():
     """batch 16, 16 q heads / 2 KV heads, d64, 8192 tokens, C = 64 of 128 blocks resident at start."""
     w = CONFIGS["1b"]
