@@ -128,7 +128,7 @@ int nosa_set_merge_in_kernel(nosa_ctx* ctx, int on);
 int nosa_set_overlap(nosa_ctx* ctx, int overlap);
 
 /* Size of the gather kernel's persistent grid (default 512, capped by the number of units).  Each
- * workgroup keeps 16 KiB of host reads in flight: more workgroups raise the link throughput (36 GB/s
+ * workgroup keeps 4 KiB of host reads in flight (16 KiB when there are fewer than 256): more workgroups raise the link throughput (36 GB/s
  * at 16, 52 at 64, 56 at 512 on PCIe Gen5 x16) but slow HBM reads of kernels that run beside it.   */
 int nosa_set_fetch_workgroups(nosa_ctx* ctx, int workgroups);
 

@@ -2,8 +2,13 @@
 // host_to_device_communication): a gather kernel whose lanes read 16 bytes each straight from
 // pinned host memory (the GPU addresses it over the host link) and write the block's slot in the
 // paged pool.  A block's keys and values are contiguous 8-32 KiB pieces, so every wave-load is a
-// 1 KiB contiguous read; all loads of a piece are issued before the first store so that many
-// requests are in flight on the link.  The list lengths live on the device; nothing is read back.
+// 1 KiB contiguous read.  The list lengths live on the device; nothing is read back.
+// Two regimes.  Every unit misses several blocks (pool = budget): with 256 workgroups or more the link is
+// saturated by their number alone, each with one 16-byte load per lane in flight (4 KiB per workgroup; four
+// loads per lane measured the same rate at best and 1-3 % less in most runs); fewer workgroups (small batches)
+// keep four loads per lane in flight.  A unit misses one block (pool with room to spare):
+// the gather is a handful of blocks and its duration is latency, so that block's keys, values and bias are
+// requested together, one round trip instead of nine.
 // The stores into the pool are non-temporal: written normally, the 80 MB of a step at the 8B shape stay
 // behind as dirty lines in the L2s and the memory-side cache, and their write-back then competes with the
 // reads of the attention kernel that follows (measured: 179 us instead of 163 us for that kernel).
@@ -34,41 +39,75 @@ struct FetchArgs {
   int bias_vec;    // 16-byte vectors per bias block
 };
 
+// A contiguous piece, DEPTH 16-byte loads per lane in flight.  Whole passes carry no per-lane conditions, so
+// nothing separates their loads.
+template <int DEPTH>
 __device__ __forceinline__ void copy_piece(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int nvec, int tid) {
-  for (int base = 0; base < nvec; base += kThreads * kInFlight) {
-    u32x4 buf[kInFlight];
+  int base = 0;
+  if constexpr (DEPTH > 1) {
+    for (; base + kThreads * DEPTH <= nvec; base += kThreads * DEPTH) {
+      u32x4 buf[DEPTH];
 #pragma unroll
-    for (int i = 0; i < kInFlight; ++i) {
-      const int x = base + i * kThreads + tid;
-      if (x < nvec) buf[i] = __builtin_nontemporal_load(src + x);
-    }
+      for (int i = 0; i < DEPTH; ++i) buf[i] = __builtin_nontemporal_load(src + base + i * kThreads + tid);
 #pragma unroll
-    for (int i = 0; i < kInFlight; ++i) {
-      const int x = base + i * kThreads + tid;
-      if (x < nvec) __builtin_nontemporal_store(buf[i], dst + x);
+      for (int i = 0; i < DEPTH; ++i) __builtin_nontemporal_store(buf[i], dst + base + i * kThreads + tid);
     }
   }
+  for (int x = base + tid; x < nvec; x += kThreads) __builtin_nontemporal_store(__builtin_nontemporal_load(src + x), dst + x);
+}
+
+// One block, keys, values and bias together: all its loads are issued before the first store (32 KiB and the
+// bias in flight for d = 128 bf16 rows).  Whole passes only (the caller checks the shape).  Measured at the 8B
+// shape with 96 slots, where a step fetches 3 blocks in all: 7.9 us for the launch instead of 14.1 us.
+template <int N>   // 16-byte loads per lane, for K and again for V, before the stores start
+__device__ __forceinline__ void copy_block(const FetchArgs& a, size_t src, size_t dst, int tid) {
+  const u32x4* __restrict__ sk = a.host_k + src * a.block_vec;
+  const u32x4* __restrict__ sv = a.host_v + src * a.block_vec;
+  u32x4* __restrict__ dk = a.pool_k + dst * a.block_vec;
+  u32x4* __restrict__ dv = a.pool_v + dst * a.block_vec;
+  const bool has_bias = a.host_bias != nullptr && tid < a.bias_vec;
+  u32x4 bb = {0u, 0u, 0u, 0u};
+  if (has_bias) bb = __builtin_nontemporal_load(a.host_bias + src * a.bias_vec + tid);
+  for (int base = 0; base < a.block_vec; base += kThreads * N) {
+    u32x4 kb[N], vb[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) kb[i] = __builtin_nontemporal_load(sk + base + i * kThreads + tid);
+#pragma unroll
+    for (int i = 0; i < N; ++i) vb[i] = __builtin_nontemporal_load(sv + base + i * kThreads + tid);
+#pragma unroll
+    for (int i = 0; i < N; ++i) __builtin_nontemporal_store(kb[i], dk + base + i * kThreads + tid);
+#pragma unroll
+    for (int i = 0; i < N; ++i) __builtin_nontemporal_store(vb[i], dv + base + i * kThreads + tid);
+  }
+  if (has_bias) __builtin_nontemporal_store(bb, a.pool_bias + dst * a.bias_vec + tid);
 }
 
 // A persistent grid: workgroup w takes units w, w + gridDim.x, ... and copies each unit's listed
-// blocks in turn, 16 KiB in flight per workgroup.  Measured on MI355X (PCIe Gen5 x16): 16 workgroups
+// blocks in turn.  Measured on MI355X (PCIe Gen5 x16): 16 workgroups
 // reach 36 GB/s, 64 reach 52 GB/s, 512 reach 56 GB/s (read latency under load is several microseconds,
 // so about 1 MiB has to be in flight).  Host reads in flight slow HBM reads of kernels running at
 // the same time (global, not per CU or per XCD): the attention over resident blocks that overlaps the
 // gather runs 1.3x slower at 64 workgroups and ~8x slower at 512 -- but it still ends before the
 // gather does, so the step time is lowest with the widest gather.
+template <int DEPTH>
 __global__ __launch_bounds__(kThreads) void fetch_kernel(const FetchArgs a, int units) {
   for (int unit = blockIdx.x; unit < units; unit += gridDim.x) {
     const int n = min(a.n_load[unit], a.k_blocks);
+    const bool lone = n == 1 && a.block_vec % (kThreads * 2) == 0 && a.bias_vec <= kThreads;
     for (int i = 0; i < n; ++i) {
       const int J = a.load_list[((size_t)unit * a.k_blocks + i) * 2];
       const int s = a.load_list[((size_t)unit * a.k_blocks + i) * 2 + 1];
       if (J < 0 || J >= a.max_blocks || s < 0 || s >= a.gpu_slots) continue;   // malformed entry: skip, never fault
       const size_t src = (size_t)unit * a.max_blocks + J;
       const size_t dst = (size_t)unit * a.gpu_slots + s;
-      copy_piece(a.host_k + src * a.block_vec, a.pool_k + dst * a.block_vec, a.block_vec, threadIdx.x);
-      copy_piece(a.host_v + src * a.block_vec, a.pool_v + dst * a.block_vec, a.block_vec, threadIdx.x);
-      if (a.host_bias) copy_piece(a.host_bias + src * a.bias_vec, a.pool_bias + dst * a.bias_vec, a.bias_vec, threadIdx.x);
+      if (lone) {
+        if (a.block_vec % (kThreads * 4) == 0) copy_block<4>(a, src, dst, threadIdx.x);
+        else copy_block<2>(a, src, dst, threadIdx.x);   // d = 64 in bf16
+        break;
+      }
+      copy_piece<DEPTH>(a.host_k + src * a.block_vec, a.pool_k + dst * a.block_vec, a.block_vec, threadIdx.x);
+      copy_piece<DEPTH>(a.host_v + src * a.block_vec, a.pool_v + dst * a.block_vec, a.block_vec, threadIdx.x);
+      if (a.host_bias) copy_piece<DEPTH>(a.host_bias + src * a.bias_vec, a.pool_bias + dst * a.bias_vec, a.bias_vec, threadIdx.x);
     }
   }
 }
@@ -138,7 +177,10 @@ int launch_fetch(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const vo
               p.block_size * p.head_dim * es / 16, p.block_size * 4 / 16};
   const int wgs = ctx->fetch_wgs < ctx->units ? ctx->fetch_wgs : ctx->units;
   TimedLaunch tl(ctx, NOSA_KERNEL_FETCH, stream);
-  hipLaunchKernelGGL(fetch_kernel, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units);
+  // few workgroups: each has to keep more of the link's latency covered by itself
+  if (wgs >= 256) hipLaunchKernelGGL(fetch_kernel<1>, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units);
+  else if (a.block_vec % (kThreads * 4) == 0) hipLaunchKernelGGL(fetch_kernel<4>, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units);
+  else hipLaunchKernelGGL(fetch_kernel<2>, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units);   // d = 64 in bf16: 8 KiB pieces
   NOSA_HIP(ctx, hipGetLastError());
   return NOSA_OK;
 }
