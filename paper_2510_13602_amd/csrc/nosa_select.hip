@@ -4,7 +4,8 @@
 //
 // Exact top-k without sorting: scores are mapped to order-preserving 32-bit keys held in registers
 // (block r*64 + lane in register r of a lane), and the k-th largest key is found by a bitwise
-// binary search (32 rounds of "how many keys >= x", counted with wave ballots on the scalar unit).
+// binary search (at most 32 rounds of "how many keys >= x", counted with wave ballots on the scalar unit; it
+// stops once exactly k keys pass, after ~14 rounds for scores of order one).
 // Keys above the threshold are taken; ties at the threshold are taken in ascending block order, which realises "the lower index wins".  The query-aware pass runs
 // first, its winners are removed, then the query-agnostic pass fills the rest of the budget.
 // Gamma(t) is emitted in ascending order by a ballot prefix scan over the selection flags; the
@@ -99,17 +100,15 @@ __device__ __forceinline__ void select_sync() {
 // sq / se: the unit's block-level scores, indexed by block (global memory or LDS).
 // R = ceil(max_blocks / 64): candidate keys per lane, register resident.
 template <int R, bool ONE_WAVE_OF_MANY>
-__device__ __forceinline__ void select_unit(const SelectArgs& a, const int unit, const int lane, const float* sq,
-                                            const float* se, unsigned char* smem) {
+__device__ __forceinline__ void select_unit(const SelectArgs& a, const int unit, const int lane, const int n_tok,
+                                            const float* sq, const float* se, unsigned char* smem) {
   int32_t* miss = (int32_t*)smem;                       // [K]
   int32_t* victim = miss + a.k_blocks;                  // [K]
   uint8_t* flags = (uint8_t*)(victim + a.k_blocks);     // [R*64] 0 none, 1 forced, 2 query-aware, 3 query-agnostic
   uint8_t* vflags = flags + R * kWave;                  // [R*64] victim_policy 1: slots chosen as victims
 
-  const int b = unit / a.n_kv_heads;
   const int K = a.k_blocks;
-  int T = a.n_tokens[b];
-  T = max(0, min(T, a.max_blocks * kBlockTokens));
+  const int T = max(0, min(n_tok, a.max_blocks * kBlockTokens));
   const int N = (T + kBlockTokens - 1) / kBlockTokens;
   const int Nc = T / kBlockTokens;
 
@@ -250,7 +249,7 @@ __global__ __launch_bounds__(kWave) void select_kernel(const SelectArgs a) {
   const int b = unit / a.n_kv_heads;
   const float* sq = a.sq_blk + (size_t)unit * a.max_blocks;
   const float* se = a.se_blk + ((size_t)(b / a.se_unit_div) * a.n_kv_heads + unit % a.n_kv_heads) * a.se_stride;
-  select_unit<R, false>(a, unit, threadIdx.x, sq, se, smem);
+  select_unit<R, false>(a, unit, threadIdx.x, a.n_tokens[b], sq, se, smem);
 }
 
 // ---- scores + selection + load positions in one launch (Alg. 1 Stage 1 as a whole) ---------------
@@ -343,7 +342,7 @@ __global__ __launch_bounds__(kFusedThreads) void score_select_kernel(const Score
   }
   __syncthreads();                       // every wavefront is still here: the scores are complete
   if (wave != 0) return;
-  select_unit<R, true>(a.sel, unit, lane, s_sq, s_se, sel_smem);
+  select_unit<R, true>(a.sel, unit, lane, T, s_sq, s_se, sel_smem);
 }
 
 }  // namespace
@@ -357,12 +356,14 @@ int launch_select(nosa_ctx* ctx, const float* sq_blk, const float* se_blk, const
                p.victim_policy, se_unit_div, se_stride > 0 ? se_stride : p.max_blocks};
   int regs = (p.max_blocks + kWave - 1) / kWave;
   if (p.victim_policy == 1 && (p.gpu_slots + kWave - 1) / kWave > regs) regs = (p.gpu_slots + kWave - 1) / kWave;
-  const int R = regs <= 8 ? 8 : regs <= 16 ? 16 : regs <= 32 ? 32 : 64;
+  const int R = regs <= 2 ? 2 : regs <= 4 ? 4 : regs <= 8 ? 8 : regs <= 16 ? 16 : regs <= 32 ? 32 : 64;
   NOSA_REQUIRE(ctx, regs <= 64, NOSA_ESHAPE, "selection supports at most %d blocks per unit", kMaxSelectBlocks);
   const size_t smem = (size_t)p.k_blocks * 8 + 2 * (size_t)R * kWave;
   const dim3 grid(ctx->units * batch_mul), block(kWave);   // batch_mul > 1: one virtual batch element per query position
   TimedLaunch tl(ctx, NOSA_KERNEL_SELECT, ctx->main);
   switch (R) {
+    case 2: hipLaunchKernelGGL(select_kernel<2>, grid, block, smem, ctx->main, a); break;
+    case 4: hipLaunchKernelGGL(select_kernel<4>, grid, block, smem, ctx->main, a); break;
     case 8: hipLaunchKernelGGL(select_kernel<8>, grid, block, smem, ctx->main, a); break;
     case 16: hipLaunchKernelGGL(select_kernel<16>, grid, block, smem, ctx->main, a); break;
     case 32: hipLaunchKernelGGL(select_kernel<32>, grid, block, smem, ctx->main, a); break;
@@ -386,13 +387,15 @@ int launch_score_select(nosa_ctx* ctx, const void* q, const void* k_pooled, cons
   int regs = (p.max_blocks + kWave - 1) / kWave;
   if (p.victim_policy == 1 && (p.gpu_slots + kWave - 1) / kWave > regs) regs = (p.gpu_slots + kWave - 1) / kWave;
   NOSA_REQUIRE(ctx, regs <= 16, NOSA_ESHAPE, "fused score + selection supports at most 1024 blocks per unit");
-  const int R = regs <= 8 ? 8 : 16;
+  const int R = regs <= 2 ? 2 : regs <= 4 ? 4 : regs <= 8 ? 8 : 16;
   const size_t smem = 2 * (size_t)p.max_blocks * sizeof(float) + (size_t)p.k_blocks * 8 + 2 * (size_t)R * kWave;
   const dim3 grid(ctx->units), block(kFusedThreads);
   TimedLaunch tl(ctx, NOSA_KERNEL_SELECT, ctx->main);
 #define NOSA_SS(DT, DD)                                                                                        \
   do {                                                                                                         \
-    if (R == 8) hipLaunchKernelGGL((score_select_kernel<DT, DD, 8>), grid, block, smem, ctx->main, a);          \
+    if (R == 2) hipLaunchKernelGGL((score_select_kernel<DT, DD, 2>), grid, block, smem, ctx->main, a);          \
+    else if (R == 4) hipLaunchKernelGGL((score_select_kernel<DT, DD, 4>), grid, block, smem, ctx->main, a);     \
+    else if (R == 8) hipLaunchKernelGGL((score_select_kernel<DT, DD, 8>), grid, block, smem, ctx->main, a);     \
     else hipLaunchKernelGGL((score_select_kernel<DT, DD, 16>), grid, block, smem, ctx->main, a);                \
   } while (0)
   if (p.dtype == NOSA_DTYPE_BF16) {
