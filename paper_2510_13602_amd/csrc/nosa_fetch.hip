@@ -12,6 +12,8 @@
 // The stores into the pool are non-temporal: written normally, the 80 MB of a step at the 8B shape stay
 // behind as dirty lines in the L2s and the memory-side cache, and their write-back then competes with the
 // reads of the attention kernel that follows (measured: 179 us instead of 163 us for that kernel).
+#include <algorithm>
+
 #include "nosa_device.h"
 #include "nosa_internal.h"
 
@@ -89,12 +91,17 @@ __device__ __forceinline__ void copy_block(const FetchArgs& a, size_t src, size_
 // the same time (global, not per CU or per XCD): the attention over resident blocks that overlaps the
 // gather runs 1.3x slower at 64 workgroups and ~8x slower at 512 -- but it still ends before the
 // gather does, so the step time is lowest with the widest gather.
+// With fewer units than workgroups a unit's list is shared by `share` workgroups (entry i goes to workgroup
+// i % share of the unit), so that small batches still put enough requests on the link (1B shape, 32 units:
+// 76 -> 72 us).  More requests per workgroup instead (four loads per lane, or whole blocks at once) measured
+// 5-10 % slower at every shape: the link wants many shallow streams.
 template <int DEPTH>
-__global__ __launch_bounds__(kThreads) void fetch_kernel(const FetchArgs a, int units) {
-  for (int unit = blockIdx.x; unit < units; unit += gridDim.x) {
+__global__ __launch_bounds__(kThreads) void fetch_kernel(const FetchArgs a, int units, int share) {
+  for (int item = blockIdx.x; item < units * share; item += gridDim.x) {
+    const int unit = item / share, part = item % share;
     const int n = min(a.n_load[unit], a.k_blocks);
     const bool lone = n == 1 && a.block_vec % (kThreads * 2) == 0 && a.bias_vec <= kThreads;
-    for (int i = 0; i < n; ++i) {
+    for (int i = part; i < n; i += share) {
       const int J = a.load_list[((size_t)unit * a.k_blocks + i) * 2];
       const int s = a.load_list[((size_t)unit * a.k_blocks + i) * 2 + 1];
       if (J < 0 || J >= a.max_blocks || s < 0 || s >= a.gpu_slots) continue;   // malformed entry: skip, never fault
@@ -103,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void fetch_kernel(const FetchArgs a, int 
       if (lone) {
         if (a.block_vec % (kThreads * 4) == 0) copy_block<4>(a, src, dst, threadIdx.x);
         else copy_block<2>(a, src, dst, threadIdx.x);   // d = 64 in bf16
-        break;
+        continue;
       }
       copy_piece<DEPTH>(a.host_k + src * a.block_vec, a.pool_k + dst * a.block_vec, a.block_vec, threadIdx.x);
       copy_piece<DEPTH>(a.host_v + src * a.block_vec, a.pool_v + dst * a.block_vec, a.block_vec, threadIdx.x);
@@ -175,12 +182,16 @@ int launch_fetch(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const vo
   FetchArgs a{(const u32x4*)host_k, (const u32x4*)host_v, (const u32x4*)host_bias, (u32x4*)pool_k, (u32x4*)pool_v,
               (u32x4*)pool_bias, load_list, n_load, p.k_blocks, p.gpu_slots, p.max_blocks,
               p.block_size * p.head_dim * es / 16, p.block_size * 4 / 16};
-  const int wgs = ctx->fetch_wgs < ctx->units ? ctx->fetch_wgs : ctx->units;
+  int share = 1;
+  if (ctx->units < ctx->fetch_wgs) share = std::max(1, std::min(ctx->fetch_wgs / ctx->units, std::max(1, p.kq_blocks)));
+  const int items = ctx->units * share;
+  const int wgs = ctx->fetch_wgs < items ? ctx->fetch_wgs : items;
+  const int depth = wgs >= 256 ? 1 : 4;
   TimedLaunch tl(ctx, NOSA_KERNEL_FETCH, stream);
   // few workgroups: each has to keep more of the link's latency covered by itself
-  if (wgs >= 256) hipLaunchKernelGGL(fetch_kernel<1>, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units);
-  else if (a.block_vec % (kThreads * 4) == 0) hipLaunchKernelGGL(fetch_kernel<4>, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units);
-  else hipLaunchKernelGGL(fetch_kernel<2>, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units);   // d = 64 in bf16: 8 KiB pieces
+  if (depth == 1) hipLaunchKernelGGL(fetch_kernel<1>, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units, share);
+  else if (a.block_vec % (kThreads * 4) == 0) hipLaunchKernelGGL(fetch_kernel<4>, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units, share);
+  else hipLaunchKernelGGL(fetch_kernel<2>, dim3(wgs), dim3(kThreads), 0, stream, a, ctx->units, share);   // d = 64 in bf16: 8 KiB pieces
   NOSA_HIP(ctx, hipGetLastError());
   return NOSA_OK;
 }
