@@ -232,6 +232,8 @@ def longgen_bench(args):
     ctx = nosa.Nosa(params, stream=stream, device=dev)
     ctx.set_fused_select(not args.no_fused_select)
     ctx.set_attention_kernel(args.attention_kernel)
+    if args.fetch_wgs:
+        ctx.set_fetch_workgroups(args.fetch_wgs)
     layers, streams = [], []
     for l in range(L):
         lay = make_layer(w, args.seed, l, device=dev)

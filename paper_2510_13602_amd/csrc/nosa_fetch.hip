@@ -39,6 +39,7 @@ struct FetchArgs {
   int k_blocks, gpu_slots, max_blocks;
   int block_vec;   // 16-byte vectors per K (or V) block
   int bias_vec;    // 16-byte vectors per bias block
+  int use_lone;    // a unit's lone block as one request: only when the gather has the GPU to itself
 };
 
 // A contiguous piece, DEPTH 16-byte loads per lane in flight.  Whole passes carry no per-lane conditions, so
@@ -60,7 +61,9 @@ __device__ __forceinline__ void copy_piece(const u32x4* __restrict__ src, u32x4*
 
 // One block, keys, values and bias together: all its loads are issued before the first store (32 KiB and the
 // bias in flight for d = 128 bf16 rows).  Whole passes only (the caller checks the shape).  Measured at the 8B
-// shape with 96 slots, where a step fetches 3 blocks in all: 7.9 us for the launch instead of 14.1 us.
+// shape with 96 slots, where a step fetches 3 blocks in all: 7.9 us for the launch instead of 14.1 us.  Used
+// only when the gather runs on the main stream: beside an attention launch the deeper requests cost that launch
+// more than they save (long generation, 68 blocks: 0.173 instead of 0.162 ms per step).
 template <int N>   // 16-byte loads per lane, for K and again for V, before the stores start
 __device__ __forceinline__ void copy_block(const FetchArgs& a, size_t src, size_t dst, int tid) {
   const u32x4* __restrict__ sk = a.host_k + src * a.block_vec;
@@ -91,16 +94,16 @@ __device__ __forceinline__ void copy_block(const FetchArgs& a, size_t src, size_
 // the same time (global, not per CU or per XCD): the attention over resident blocks that overlaps the
 // gather runs 1.3x slower at 64 workgroups and ~8x slower at 512 -- but it still ends before the
 // gather does, so the step time is lowest with the widest gather.
-// With fewer units than workgroups a unit's list is shared by `share` workgroups (entry i goes to workgroup
+// With fewer than 256 units a unit's list is shared by `share` workgroups (entry i goes to workgroup
 // i % share of the unit), so that small batches still put enough requests on the link (1B shape, 32 units:
-// 76 -> 72 us).  More requests per workgroup instead (four loads per lane, or whole blocks at once) measured
+// 76 -> 72 us); beyond about 256 workgroups more of them only slow the attention launch running beside.  More requests per workgroup instead (four loads per lane, or whole blocks at once) measured
 // 5-10 % slower at every shape: the link wants many shallow streams.
 template <int DEPTH>
 __global__ __launch_bounds__(kThreads) void fetch_kernel(const FetchArgs a, int units, int share) {
   for (int item = blockIdx.x; item < units * share; item += gridDim.x) {
     const int unit = item / share, part = item % share;
     const int n = min(a.n_load[unit], a.k_blocks);
-    const bool lone = n == 1 && a.block_vec % (kThreads * 2) == 0 && a.bias_vec <= kThreads;
+    const bool lone = n == 1 && a.use_lone && a.block_vec % (kThreads * 2) == 0 && a.bias_vec <= kThreads;
     for (int i = part; i < n; i += share) {
       const int J = a.load_list[((size_t)unit * a.k_blocks + i) * 2];
       const int s = a.load_list[((size_t)unit * a.k_blocks + i) * 2 + 1];
@@ -181,9 +184,9 @@ int launch_fetch(nosa_ctx* ctx, hipStream_t stream, const void* host_k, const vo
   const int es = p.dtype == NOSA_DTYPE_F32 ? 4 : 2;
   FetchArgs a{(const u32x4*)host_k, (const u32x4*)host_v, (const u32x4*)host_bias, (u32x4*)pool_k, (u32x4*)pool_v,
               (u32x4*)pool_bias, load_list, n_load, p.k_blocks, p.gpu_slots, p.max_blocks,
-              p.block_size * p.head_dim * es / 16, p.block_size * 4 / 16};
+              p.block_size * p.head_dim * es / 16, p.block_size * 4 / 16, stream == ctx->main ? 1 : 0};
   int share = 1;
-  if (ctx->units < ctx->fetch_wgs) share = std::max(1, std::min(ctx->fetch_wgs / ctx->units, std::max(1, p.kq_blocks)));
+  if (ctx->units < 256 && ctx->fetch_wgs >= 256) share = std::max(1, std::min(256 / ctx->units, std::max(1, p.kq_blocks)));
   const int items = ctx->units * share;
   const int wgs = ctx->fetch_wgs < items ? ctx->fetch_wgs : items;
   const int depth = wgs >= 256 ? 1 : 4;
