@@ -96,14 +96,23 @@ __device__ __forceinline__ void copy_block(const FetchArgs& a, size_t src, size_
 // gather does, so the step time is lowest with the widest gather.
 // With fewer than 256 units a unit's list is shared by `share` workgroups (entry i goes to workgroup
 // i % share of the unit), so that small batches still put enough requests on the link (1B shape, 32 units:
-// 76 -> 72 us); beyond about 256 workgroups more of them only slow the attention launch running beside.  More requests per workgroup instead (four loads per lane, or whole blocks at once) measured
-// 5-10 % slower at every shape: the link wants many shallow streams.
+// 76 -> 72 us); beyond about 256 workgroups more of them only slow the attention launch running beside.  More requests per
+// workgroup instead (four loads per lane, or whole blocks at once) measured 5-10 % slower at every shape: the
+// link wants many shallow streams.
 template <int DEPTH>
 __global__ __launch_bounds__(kThreads) void fetch_kernel(const FetchArgs a, int units, int share) {
   for (int item = blockIdx.x; item < units * share; item += gridDim.x) {
     const int unit = item / share, part = item % share;
     const int n = min(a.n_load[unit], a.k_blocks);
-    const bool lone = n == 1 && a.use_lone && a.block_vec % (kThreads * 2) == 0 && a.bias_vec <= kThreads;
+    // A lone block travels as one request only when misses are rare around it (at most 2 of the 64 units this
+    // one sits among fetch anything): with a lone block in every second or third unit the deeper requests
+    // lower the link's rate instead (8B shape with 80 slots, 0.42 blocks per unit and step: 152 against 129 us).
+    bool lone = false;
+    if (n == 1 && a.use_lone && a.block_vec % (kThreads * 2) == 0 && a.bias_vec <= kThreads) {
+      const int u = (unit & ~(kWave - 1)) + (int)(threadIdx.x % kWave);
+      const bool busy = u < units && a.n_load[u] > 0;
+      lone = __popcll(__ballot(busy)) <= 2;
+    }
     for (int i = part; i < n; i += share) {
       const int J = a.load_list[((size_t)unit * a.k_blocks + i) * 2];
       const int s = a.load_list[((size_t)unit * a.k_blocks + i) * 2 + 1];
