@@ -584,6 +584,12 @@ def main():
         sub = measure(a2, w.replace(gpu_slots=96, victim_policy=1))
         line["larger_pool"] = {k: sub[k] for k in ("value", "unit", "ms_per_step", "steps", "warmup", "config", "roofline", "kernels_avg_us",
                                                     "step_hbm_GBps", "step_roofline", "locality", "fetch")}
+        if args.mode != "graph":
+            # ... and the same steps as one HIP graph replay each (no event pairs, no launch gaps)
+            a3 = argparse.Namespace(**vars(a2))
+            a3.mode, a3.locality_steps = "graph", 0
+            g = measure(a3, w.replace(gpu_slots=96, victim_policy=1))
+            line["larger_pool"]["graph_replay"] = {k: g[k] for k in ("value", "unit", "ms_per_step", "step_hbm_GBps", "step_roofline")}
     print(json.dumps(line), flush=True)
 
 
