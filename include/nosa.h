@@ -121,10 +121,13 @@ int nosa_set_attention_kernel(nosa_ctx* ctx, int which);
  * waits); 0 a separate combine launch.  Same arithmetic in the same order, same result.           */
 int nosa_set_merge_in_kernel(nosa_ctx* ctx, int on);
 
-/* overlap = 1 (default): fetches run on the context's own stream; a nosa_sparse_decode that follows
+/* overlap = 1: fetches run on the context's own stream; a nosa_sparse_decode that follows
  * a nosa_fetch first attends the selected blocks that are not in that fetch's load list, then waits
  * for the fetch, attends the fetched blocks and merges.  overlap = 0: everything is enqueued on the
- * main stream in call order (used to check that both orders give the same result).               */
+ * main stream in call order.  Same selections, outputs equal up to the summation order of the merge.
+ * Default: 1 when the selected keys and values of a step (units x K x block x d x 2) are at least
+ * 320 MB, else 0 -- the second attention launch and the cross-stream waits cost about 28 us per step,
+ * which the hidden attention time has to exceed (8B shape: 1.62 -> 1.50 ms; 1B shape: 0.116 -> 0.144). */
 int nosa_set_overlap(nosa_ctx* ctx, int overlap);
 
 /* Size of the gather kernel's persistent grid (default 512, capped by the number of units).  Each

@@ -127,6 +127,13 @@ int nosa_create(nosa_ctx** out, const nosa_params* p, void* main_stream) {
   ctx->scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
   ctx->main = (hipStream_t)main_stream;
   ctx->splits = nosa::decode_default_splits(*p);
+  {
+    // The gather beside the attention costs a fixed ~28 us of cross-stream waits and a second attention launch
+    // per step and hides the attention over the resident blocks: it pays once that attention streams for longer
+    // (from about 320 MB of selected keys and values per step on).  nosa_set_overlap overrides.
+    const double kv_bytes = 2.0 * ctx->units * p->k_blocks * p->block_size * p->head_dim * (p->dtype == NOSA_DTYPE_F32 ? 4 : 2);
+    ctx->overlap = kv_bytes >= 320e6 ? 1 : 0;
+  }
   auto bail = [&](const char* what, hipError_t e) {
     set_error(nullptr, NOSA_EHIP, "%s failed: %s", what, hipGetErrorString(e));
     nosa_destroy(ctx);

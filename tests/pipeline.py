@@ -338,6 +338,7 @@ def run_growing(w: Workload, seed: int, steps: int, device="cuda:0", margin=1e-3
     n_tok = np.full((w.batch,), w.context, np.int32)
     ol = OracleLayer(w, to_np(layer["host_k"]).copy(), to_np(layer["host_v"]).copy(), to_np(layer["host_bias"]).copy(), n_tok)
     ctx = nosa.Nosa(gpu_params(w), device=device)
+    ctx.set_overlap(True)                        # whatever the shape's default: the two-launch order is the one under test here
     gl = LayerCache(ctx, pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"]),
                     torch.from_numpy(n_tok))
     gl.rebuild_pooled()

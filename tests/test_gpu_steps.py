@@ -149,6 +149,7 @@ def _two_layers(w, seed, stream=None):
     from paper_2510_13602_amd.runtime import LayerCache, pinned_like
     layer = make_layer(w, seed, 0)
     ctx = nosa.Nosa(gpu_params(w), stream=stream)
+    ctx.set_overlap(True)      # the two-launch order with the side-stream gather, whatever the shape's default
     hk, hv, hb = pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"])
     n_tok = torch.full((w.batch,), w.context, dtype=torch.int32)
     a, b = LayerCache(ctx, hk, hv, hb, n_tok), LayerCache(ctx, hk, hv, hb, n_tok)
@@ -225,6 +226,7 @@ def test_fused_stage1_degenerate_token_counts():
                                 sink_blocks=1, window_blocks=1, gpu_slots=7, dtype="bf16", head_dim=128)
     layer = make_layer(w, 12, 0)
     ctx = nosa.Nosa(gpu_params(w))
+    ctx.set_overlap(True)
     hk, hv, hb = pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"])
     n_tok = torch.tensor(tokens, dtype=torch.int32)
     a, b = LayerCache(ctx, hk, hv, hb, n_tok), LayerCache(ctx, hk, hv, hb, n_tok)
@@ -294,6 +296,7 @@ def test_graph_of_a_generation_step_replays_like_eager():
     with torch.cuda.stream(s):
         layer = make_layer(w, 31, 0)
         ctx = nosa.Nosa(gpu_params(w), stream=s)
+        ctx.set_overlap(True)
         n_tok = torch.full((B,), w.context, dtype=torch.int32)
         twins = []
         for _ in range(2):                        # each twin appends into its own host pool
@@ -384,6 +387,7 @@ def test_degenerate_token_counts_per_batch_element(K, Kq, Ns, Nw, tokens):
     pb = np.zeros((B, H, C, nb), np.float32)
     sob, bos = np.full((B, H, w.max_blocks), -1, np.int32), np.full((B, H, C), -1, np.int32)
     ctx = nosa.Nosa(gpu_params(w))
+    ctx.set_overlap(True)
     gl = LayerCache(ctx, pinned_like(layer["host_k"]), pinned_like(layer["host_v"]), pinned_like(layer["host_bias"]),
                     torch.from_numpy(n_tok))
     gl.rebuild_pooled()
