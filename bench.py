@@ -654,7 +654,7 @@ def measure(args, w):
     # queries: one stream per host pool (the planted directions belong to the pool)
     streams = [QueryStream(w, args.seed, hl, device=dev) for hl in range(LH)]
     total = args.warmup + args.steps
-    n_q = 1 if args.resident else (2 * total + 16 + args.locality_steps) // L + 4
+    n_q = 1 if args.resident else (3 * total + 32 + args.locality_steps) // L + 4
     queries = [[streams[hl].next(t) for t in range(n_q)] for hl in range(LH)]
 
     def q_of(l, i):
@@ -662,7 +662,7 @@ def measure(args, w):
         # correlation of the AR(1) workloads); i counts steps over all layers
         return queries[l % LH][0 if args.resident else (i + L - 1) // L]
 
-    q_static = [torch.zeros_like(queries[0][0]) for _ in range(L)] if args.mode == "graph" else None
+    q_static = [torch.zeros_like(queries[0][0]) for _ in range(L)]    # what a layer's graph reads its query from
 
     def do_step(l, q):
         if args.gap_cycles:                         # experiment: an almost idle GPU for a while before every step
@@ -730,11 +730,26 @@ def measure(args, w):
             do_step(j % L, q_of(j % L, 1 + j))
             step_no[0] += 1
         dt_ov, kern_ov = timed_region(args.steps)
+        # ... and the same order as one HIP graph replay per step: the cross-stream waits become graph edges
+        for l, lc in enumerate(layers):
+            lc.capture(q_static[l])
+        torch.cuda.synchronize()
+        args.mode = "graph"
+        for _ in range(min(8, args.warmup)):
+            j = step_no[0]
+            do_step(j % L, q_of(j % L, 1 + j))
+            step_no[0] += 1
+        dt_og, _ = timed_region(args.steps)
         ctx.set_overlap(False)
+        if mode == "graph":                      # back to the graphs of the one-stream order
+            for l, lc in enumerate(layers):
+                lc.capture(q_static[l])
+            torch.cuda.synchronize()
         args.mode = mode
         overlap = {"ms_per_step": 1e3 * dt_ov / args.steps, "value": w.units * args.steps / dt_ov, "kernels_avg_us": kern_ov,
+                   "graph_replay": {"ms_per_step": 1e3 * dt_og / args.steps, "value": w.units * args.steps / dt_og},
                    "note": "gather on the side stream; sparse_decode = attention over resident blocks (runs beside the gather), "
-                           "combine = attention over fetched blocks + merge"}
+                           "combine = attention over fetched blocks + merge; graph_replay = the same steps as one graph launch each"}
 
     # locality gamma(t) = #(Gamma(t) ^ Gamma(t-1)) / #Gamma(t): with the pool holding the previous selection
     # (and whatever else fits) the blocks NOT fetched are exactly the ones found resident, so
