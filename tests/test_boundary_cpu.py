@@ -86,3 +86,13 @@ def test_no_cpu_fallback():
         pytest.skip("GPU present")
     with pytest.raises(nosa.NosaError):
         nosa.Nosa(_good())
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The path runs on one GPU; the benchmark says so instead of pretending to scale."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stderr + r.stdout)
