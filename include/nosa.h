@@ -97,7 +97,9 @@ size_t nosa_workspace_bytes(const nosa_params* p);
 int nosa_set_workspace(nosa_ctx* ctx, void* dev_ws, size_t bytes);
 
 /* Number of partial results per unit in nosa_sparse_decode (1..NOSA_MAX_SPLITS); the default is
- * chosen from the shape.  The workspace is sized for NOSA_MAX_SPLITS.                            */
+ * chosen from the shape so that the launch fills whole rounds of 512 workgroups with as few partial
+ * results as possible (1 at 512 units, 4 at 128, 5 at 96).  The workspace is sized for
+ * NOSA_MAX_SPLITS.                                                                              */
 #define NOSA_MAX_SPLITS 16
 int nosa_set_splits(nosa_ctx* ctx, int splits);
 int nosa_get_splits(const nosa_ctx* ctx);

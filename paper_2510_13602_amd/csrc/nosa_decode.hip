@@ -928,12 +928,25 @@ int decode_default_splits(const nosa_params& p) {
   const int row_bytes = p.head_dim * (p.dtype == NOSA_DTYPE_F32 ? 4 : 2);
   const int tile_tokens = kRPW * (kLoads / (row_bytes / 128));
   const int tiles = p.k_blocks * (kBlockTokens / tile_tokens);
-  int s = (512 + units - 1) / units;            // two workgroups per CU keep HBM busy; fewer splits, less merging
-  const int cap = tiles / kWaves > 1 ? tiles / kWaves : 1;   // at least one tile per wave
-  if (s > cap) s = cap;
-  if (s > NOSA_MAX_SPLITS) s = NOSA_MAX_SPLITS;
-  if (s < 1) s = 1;
-  return s;
+  // 512 workgroups (two per CU) keep HBM busy.  What a split count is worth: how full the rounds of 512 are,
+  // less a charge per extra partial result to merge and per extra round.  Fitted to measurements at the 3B
+  // shape (HIP events, us): 96 units 5 splits 41 (4: 46, 6: 52); 128 units 4: 49 (2: 51, 3: 57, 8: 58);
+  // 160 units 3: 61 (2: 77, 4: 78); 320 units 3: 118 (1: 138, 2: 139); 400 units 1: 146 (2: 156, 3: 157).
+  const int cap0 = tiles / kWaves > 1 ? tiles / kWaves : 1;   // at least one tile per wave
+  const int cap = cap0 < NOSA_MAX_SPLITS ? cap0 : NOSA_MAX_SPLITS;
+  if (units > 512) return 1;
+  if (units * cap <= 512) return cap;     // few units: as many workgroups as the tiles allow
+  int best = 1;
+  double best_score = -1e9;
+  for (int s = 1; s <= cap; ++s) {
+    const int wgs = units * s, rounds = (wgs + 511) / 512;
+    const double score = (double)wgs / (512.0 * rounds) - 0.03 * (s - 1) - 0.05 * (rounds - 1);
+    if (score > best_score + 1e-9) {
+      best_score = score;
+      best = s;
+    }
+  }
+  return best;
 }
 
 namespace {

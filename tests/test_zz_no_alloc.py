@@ -68,7 +68,7 @@ def _twin_run(w, seed, steps, overlap, splits=None):
 
 @pytest.mark.parametrize("overlap", [False, True])
 def test_static_scratch_decode_two_calls_second_smaller(overlap):
-    big = CONFIGS["1b"].replace(batch=4)                                      # 8 units x 16 splits, G = 8, d = 64
+    big = CONFIGS["1b"].replace(batch=4)                                      # 8 units x 8 splits, G = 8, d = 64
     small = CONFIGS["1b"].replace(batch=1, context=64 * 40 + 17)              # 2 units, ragged tail, 5 splits
     e1 = _twin_run(big, seed=21, steps=3, overlap=overlap)
     e2 = _twin_run(small, seed=22, steps=3, overlap=overlap, splits=5)
